@@ -1,0 +1,219 @@
+/*
+ * specvlm.h -- C ABI of the SpecVLM speculative-decode hot path on MI355X.
+ *
+ * Five operations, one per step of a speculative decode step of a video LLM
+ * over a long video KV cache (paper: arXiv 2508.16201):
+ *
+ *   specvlm_score        language-to-video attention scores   (Sec. 3.1, Eq. 4-5)
+ *   specvlm_select       Stage I top-k + Stage II uniform stride (Sec. 3.2, Eq. 6-7)
+ *   specvlm_gather_kv    the draft's pruned KV cache           (Sec. 3.2, last paragraph)
+ *   specvlm_decode_attn  draft decode / parallel verification  (Sec. 2.1)
+ *   specvlm_accept       draft-token acceptance                (Sec. 2.1; App. A greedy)
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Return value: SPECVLM_OK (0) or a negative SPECVLM_E* code.  Arguments are
+ *    validated on the host before anything is enqueued: a failed call has
+ *    launched nothing.  Nothing is printed, nothing aborts.
+ *  - Every data pointer is a DEVICE pointer owned by the caller unless it is
+ *    marked "host".  The library never allocates, frees or keeps a pointer.
+ *    Scratch memory comes from the caller as `workspace` (device, 256-byte
+ *    aligned); its required size is returned by the matching
+ *    specvlm_*_workspace_bytes query, which is host-only and pure.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return without synchronising; outputs are valid
+ *    once the stream reaches that point.  Calls that share a workspace must be
+ *    ordered on one stream.
+ *  - bf16 tensors are described by (pointer, token stride, head stride) in
+ *    ELEMENTS; the head dimension d is contiguous and rows are 16-byte aligned
+ *    (strides are multiples of 8 elements).  Both [tokens, heads, d] and
+ *    [heads, tokens, d] caches are therefore accepted without a copy.
+ *  - Supported shapes: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads;
+ *    anything else returns SPECVLM_EUNSUPPORTED.
+ *  - Ragged batches: `cu_*` are device int32 arrays of batch+1 prefix offsets
+ *    (request b owns rows [cu[b], cu[b+1]) of the concatenated tensor).  A NULL
+ *    cu pointer means batch = 1 with the scalar length arguments.  With cu
+ *    arrays the scalar length arguments are the MAXIMUM over requests (they
+ *    size the launch); the device arrays are trusted to respect them.
+ *  - Zero-size work (batch 0, no video tokens, budget 0) is legal: returns 0.
+ */
+#ifndef SPECVLM_H
+#define SPECVLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPECVLM_OK            0
+#define SPECVLM_EINVAL       (-1)  /* invalid argument (null pointer, negative size, budget > tokens, ...) */
+#define SPECVLM_EUNSUPPORTED (-2)  /* shape outside the supported set */
+#define SPECVLM_EWORKSPACE   (-3)  /* workspace missing, misaligned or too small */
+#define SPECVLM_ELAUNCH      (-4)  /* the HIP runtime refused a launch */
+
+/* Static text for a return code (host pointer, never NULL). */
+const char* specvlm_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int specvlm_version(void);
+
+/* --------------------------------------------------------------------------
+ * specvlm_score -- token scores A = {a_j}  (Sec. 3.1, Eq. 4-5).
+ *
+ * The guidance matrix G is the language-query x video-key block of the
+ * verifier's attention matrix; a_j is column j of G averaged over the language
+ * queries (Eq. 5) and over the q heads of this layer ("averaging across all
+ * layers and heads": layers are accumulated by calling once per layer with
+ * beta = 1).
+ *
+ *   q_text   bf16 [n_text, H_q, d]   language-prompt queries (RoPE already applied)
+ *   k_cache  bf16 [n_keys, H_kv, d]  this layer's keys
+ *   video keys are rows [video_start, video_start + n_video) of k_cache
+ *   text query i sits at absolute position text_pos0 + i and sees keys
+ *   j <= text_pos0 + i (causal); softmax logits are softmax_scale * q.k
+ *   norm_mode 0: rows normalised over every visible key, then sliced to the
+ *                video columns (G is a block of the full attention matrix)
+ *   norm_mode 1: rows normalised over the visible video keys only
+ *   row_lse  optional fp32 [n_text, H_q]: natural-log normaliser of each row for
+ *            the chosen norm_mode (e.g. saved by the prefill attention); when
+ *            given, the library skips its own normaliser pass
+ *   scores   fp32 [n_video]:  scores = beta * scores + (1/(H_q n_text)) sum_{h,i} G
+ *            (beta = 0 overwrites and never reads the old contents)
+ *
+ * One request per call: cu_text, cu_keys and cu_video must be NULL and batch 1
+ * (a batch is scored by one call per request); other values return
+ * SPECVLM_EUNSUPPORTED.
+ * -------------------------------------------------------------------------- */
+size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_keys, int n_video,
+                                     int n_q_heads, int n_kv_heads, int head_dim,
+                                     int have_row_lse);
+
+int specvlm_score(
+    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_select -- the two-stage retention set  (Sec. 3.2).
+ *
+ * Stage I: V_R = the k_top highest-scoring video tokens (Eq. 6 sizes V_R by
+ *   cumulative score mass; here its size is an input).  Equal scores: the
+ *   lower token index ranks first.
+ *   -0.0 equals +0.0; NaN ranks below every number.
+ * Stage II: over the remaining tokens V \ V_R in raster order (frame-major,
+ *   row-major inside a frame), keep U = keep_budget - k_top tokens at the fixed
+ *   interval I = R/U (Eq. 7 with the budget as denominator), R = n_video - k_top:
+ *   the tokens whose rank in the remainder is floor(t*R/U), t = 0..U-1.
+ * Output: keep_idx = sort(V_R u V_U), ascending, video-local, exactly
+ *   keep_budget entries per request; from_topk[m] = 1 iff keep_idx[m] is in V_R.
+ *
+ *   scores      fp32 [sum n_video_b]
+ *   cu_video    int32 [batch+1] or NULL (batch 1, n_video = max_n_video)
+ *   k_top, keep_budget   device int32 [batch]
+ *   cu_keep     device int32 [batch+1], prefix sums of keep_budget; NULL for batch 1
+ *   max_n_video, total_keep   host ints (launch shape, validation)
+ *   keep_idx    int32 [total_keep];  from_topk  uint8 [total_keep] or NULL
+ *   status      optional device int32 [batch]: SPECVLM_OK, or SPECVLM_EINVAL for a
+ *               request whose device-side budgets are inconsistent (k_top >
+ *               keep_budget, keep_budget > n_video, n_video > max_n_video); such
+ *               a request writes no indices.
+ * Limit: max_n_video <= 65536.  No workspace is needed (the query returns 0).
+ * -------------------------------------------------------------------------- */
+size_t specvlm_select_workspace_bytes(int batch, int max_n_video);
+
+int specvlm_select(
+    const float* scores, const int32_t* cu_video,
+    const int32_t* k_top, const int32_t* keep_budget, const int32_t* cu_keep,
+    int batch, int max_n_video, int total_keep,
+    int32_t* keep_idx, uint8_t* from_topk, int32_t* status,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_gather_kv -- build the draft's KV cache  (Sec. 3.2, last paragraph:
+ * the draft keeps V_R u V_U and the language prompt; Self-SD setting: same
+ * parameters, pruned KV cache).  For every layer, for K and V:
+ *
+ *   dst rows = src[0 : video_start]  ++  src[video_start + keep_idx[*]]
+ *              ++  src[video_start + n_video : n_keys]
+ *
+ * Rows are copied bit for bit.  src/dst: bf16 [n_layers, tokens, H_kv, d] with
+ * explicit layer / token / head strides (elements).  dst holds
+ * n_keys - n_video + n_keep tokens per layer.  keep_idx is device int32
+ * [n_keep], video-local, ascending (the output of specvlm_select).  dst must
+ * not overlap src.  v_src/v_dst may both be NULL to copy K only.
+ * -------------------------------------------------------------------------- */
+int specvlm_gather_kv(
+    const void* k_src, const void* v_src,
+    int64_t src_layer_stride, int64_t src_tok_stride, int64_t src_head_stride,
+    void* k_dst, void* v_dst,
+    int64_t dst_layer_stride, int64_t dst_tok_stride, int64_t dst_head_stride,
+    int n_layers, int n_keys, int video_start, int n_video,
+    const int32_t* keep_idx, int n_keep, int n_kv_heads, int head_dim, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_decode_attn -- grouped-query softmax attention of a short query
+ * block over a KV cache  (Sec. 2.1).  q_len = 1 is the draft's (or target's)
+ * plain decode; q_len = gamma + 1 is the target's parallel verification of
+ * gamma drafted tokens: the block is the last committed token followed by the
+ * drafted ones, its own K/V rows are already the last q_len rows of the cache,
+ * and request-local key j is visible to query t iff j <= kv_len - q_len + t
+ * (causal inside the block).
+ *
+ *   q    bf16 [sum q_len_b, H_q, d]      out  bf16, same shape and strides as q
+ *   k,v  bf16 [sum kv_len_b, H_kv, d]    (one token / head stride pair for both)
+ *   lse  optional fp32 [sum q_len_b, H_q]: natural log of each row's softmax sum
+ *   q head h reads kv head h / (H_q / H_kv)
+ *   num_splits: key-range splits per (request, kv head) (flash-decode);
+ *               0 lets the library choose for the shape.
+ * Limits: (H_q/H_kv) * q_len <= 64.
+ * -------------------------------------------------------------------------- */
+size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int kv_len,
+                                           int n_q_heads, int n_kv_heads, int head_dim,
+                                           int num_splits);
+
+int specvlm_decode_attn(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    void* out, float* lse, int num_splits,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_accept -- which drafted tokens survive verification  (Sec. 2.1).
+ *
+ * Greedy (draft_logits == NULL and uniforms == NULL; App. A: the target decodes
+ * greedily, output identical to the target's own): t_i = argmax of target row
+ * i, lowest index on ties; n = length of the longest prefix with
+ * draft_tokens[i] == t_i; out = x_0..x_{n-1}, t_n, then -1 padding.
+ *
+ * Rejection sampling (both given; the speculative-sampling rule the paper
+ * builds on, which preserves the target's output distribution): with p_i, q_i
+ * the softmax of target / draft row i at `temperature`, accept x_i iff
+ * u_i * q_i[x_i] < p_i[x_i], stop at the first rejection (n accepted); the
+ * final token is drawn by inverse CDF (ascending token order) with u_gamma from
+ * max(p_n - q_n, 0) if n < gamma, else from p_gamma.
+ *
+ *   target_logits fp32 [batch, gamma+1, vocab]   draft_logits fp32 [batch, gamma, vocab]
+ *   draft_tokens  int32 [batch, gamma]           uniforms     fp32 [batch, gamma+1] in [0,1)
+ *   n_accepted    int32 [batch] (0..gamma)       out_tokens   int32 [batch, gamma+1]
+ * -------------------------------------------------------------------------- */
+size_t specvlm_accept_workspace_bytes(int batch, int gamma, int vocab, int sampling);
+
+int specvlm_accept(
+    const float* target_logits, const float* draft_logits,
+    const int32_t* draft_tokens, const float* uniforms,
+    int batch, int gamma, int vocab, float temperature,
+    int32_t* n_accepted, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVLM_H */

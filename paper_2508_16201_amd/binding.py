@@ -1,0 +1,257 @@
+"""ctypes binding of ``libspecvlm.so``: argument marshalling only.
+
+Every function has the name of the C entry point it calls (``include/specvlm.h``)
+and takes torch tensors that live on the GPU; torch provides device memory and
+the current stream, nothing else.  There is no CPU fallback: if the HIP
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecvlm.so")
+_lib = None
+
+EXPORTS = (
+    "specvlm_status_string", "specvlm_version",
+    "specvlm_score_workspace_bytes", "specvlm_score",
+    "specvlm_select_workspace_bytes", "specvlm_select",
+    "specvlm_gather_kv",
+    "specvlm_decode_attn_workspace_bytes", "specvlm_decode_attn",
+    "specvlm_accept_workspace_bytes", "specvlm_accept",
+)
+
+
+class SpecVLMError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {status_string(status)} ({status})")
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library (built by ``paper_2508_16201_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2508_16201_amd.build` "
+                "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        l.specvlm_status_string.restype = C.c_char_p
+        l.specvlm_status_string.argtypes = [C.c_int]
+        l.specvlm_version.restype = C.c_int
+        for name in EXPORTS:
+            if name.endswith("_workspace_bytes"):
+                getattr(l, name).restype = C.c_size_t
+        i64, i32, f32, vp, sz = C.c_int64, C.c_int, C.c_float, C.c_void_p, C.c_size_t
+        l.specvlm_score_workspace_bytes.argtypes = [i32] * 8
+        l.specvlm_score.argtypes = [vp, i64, i64, vp, i64, i64, vp, vp, vp, i32,
+                                    i32, i32, i32, i32, i32, i32, i32, i32, f32,
+                                    i32, vp, f32, vp, vp, sz, vp]
+        l.specvlm_select_workspace_bytes.argtypes = [i32, i32]
+        l.specvlm_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        l.specvlm_gather_kv.argtypes = [vp, vp, i64, i64, i64, vp, vp, i64, i64, i64,
+                                        i32, i32, i32, i32, vp, i32, i32, i32, vp]
+        l.specvlm_decode_attn_workspace_bytes.argtypes = [i32] * 7
+        l.specvlm_decode_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
+                                          i32, i32, i32, f32, vp, vp, i32, vp, sz, vp]
+        l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
+        l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+        for name in ("specvlm_score", "specvlm_select", "specvlm_gather_kv",
+                     "specvlm_decode_attn", "specvlm_accept"):
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().specvlm_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().specvlm_version()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensors must live on the GPU")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise SpecVLMError(fn, rc)
+
+
+def new_workspace(nbytes: int, device=None) -> torch.Tensor:
+    """A 256-byte aligned device buffer (torch's caching allocator aligns to 512)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device or "cuda")
+
+
+def _ws(workspace: Optional[torch.Tensor], need: int, like: torch.Tensor) -> torch.Tensor:
+    if workspace is None:
+        workspace = new_workspace(need, like.device)
+    return workspace
+
+
+def _thd(t: torch.Tensor) -> Tuple[int, int]:
+    """(token stride, head stride) in elements of a [tokens, heads, d] view."""
+    if t.dim() != 3 or t.stride(2) != 1:
+        raise ValueError("expected a [tokens, heads, d] view with contiguous d")
+    return t.stride(0), t.stride(1)
+
+
+# --------------------------------------------------------------------------- score
+def score_workspace_bytes(n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_dim,
+                          have_row_lse=False) -> int:
+    return lib().specvlm_score_workspace_bytes(1, n_text, n_keys, n_video, n_q_heads, n_kv_heads,
+                                               head_dim, int(have_row_lse))
+
+
+def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
+          text_pos0: int, softmax_scale: float, *, norm_mode: int = 0,
+          row_lse: Optional[torch.Tensor] = None, beta: float = 0.0,
+          scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
+          ) -> torch.Tensor:
+    """q_text [L,H_q,d] bf16, k_cache [n_keys,H_kv,d] bf16 -> scores fp32 [n_video]."""
+    n_text, hq, d = q_text.shape
+    n_keys, hkv, _ = k_cache.shape
+    if scores is None:
+        scores = torch.empty(n_video, dtype=torch.float32, device=q_text.device)
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs an existing scores tensor")
+    need = score_workspace_bytes(n_text, n_keys, n_video, hq, hkv, d, row_lse is not None)
+    workspace = _ws(workspace, need, q_text)
+    qs, ks = _thd(q_text), _thd(k_cache)
+    rc = lib().specvlm_score(_ptr(q_text), qs[0], qs[1], _ptr(k_cache), ks[0], ks[1],
+                             None, None, None, 1, n_text, n_keys, video_start, n_video, text_pos0,
+                             hq, hkv, d, float(softmax_scale), norm_mode, _ptr(row_lse),
+                             float(beta), _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
+    _check("specvlm_score", rc)
+    return scores
+
+
+# -------------------------------------------------------------------------- select
+def select(scores: torch.Tensor, k_top: torch.Tensor, keep_budget: torch.Tensor, total_keep: int,
+           *, cu_video: Optional[torch.Tensor] = None, cu_keep: Optional[torch.Tensor] = None,
+           max_n_video: Optional[int] = None, want_flags: bool = True, want_status: bool = False):
+    """scores fp32 [sum V_b]; k_top/keep_budget device int32 [batch] -> keep_idx int32 [total_keep]."""
+    batch = k_top.numel()
+    if max_n_video is None:
+        if cu_video is not None:
+            raise ValueError("max_n_video is required with cu_video")
+        max_n_video = scores.numel()
+    dev = scores.device
+    keep_idx = torch.empty(total_keep, dtype=torch.int32, device=dev)
+    flags = torch.empty(total_keep, dtype=torch.uint8, device=dev) if want_flags else None
+    status = torch.empty(batch, dtype=torch.int32, device=dev) if want_status else None
+    rc = lib().specvlm_select(_ptr(scores), _ptr(cu_video), _ptr(k_top), _ptr(keep_budget),
+                              _ptr(cu_keep), batch, max_n_video, total_keep, _ptr(keep_idx),
+                              _ptr(flags), _ptr(status), None, 0, _stream())
+    _check("specvlm_select", rc)
+    out = (keep_idx, flags)
+    return out + (status,) if want_status else out
+
+
+# ----------------------------------------------------------------------- gather_kv
+def gather_kv(k_src: torch.Tensor, v_src: Optional[torch.Tensor], video_start: int, n_video: int,
+              keep_idx: torch.Tensor, k_dst: Optional[torch.Tensor] = None,
+              v_dst: Optional[torch.Tensor] = None):
+    """k_src/v_src bf16 [layers, n_keys, H_kv, d] (any layer/token/head strides, d contiguous)."""
+    if k_src.dim() != 4 or k_src.stride(3) != 1:
+        raise ValueError("expected [layers, tokens, heads, d] with contiguous d")
+    n_layers, n_keys, hkv, d = k_src.shape
+    n_keep = keep_idx.numel()
+    n_dst = n_keys - n_video + n_keep
+    if k_dst is None:
+        k_dst = torch.empty((n_layers, n_dst, hkv, d), dtype=k_src.dtype, device=k_src.device)
+    if v_src is not None and v_dst is None:
+        v_dst = torch.empty_like(k_dst)
+    if v_src is not None and v_src.stride() != k_src.stride():
+        raise ValueError("K and V must share strides")
+    if v_dst is not None and v_dst.stride() != k_dst.stride():
+        raise ValueError("K and V destinations must share strides")
+    rc = lib().specvlm_gather_kv(_ptr(k_src), _ptr(v_src), k_src.stride(0), k_src.stride(1),
+                                 k_src.stride(2), _ptr(k_dst), _ptr(v_dst), k_dst.stride(0),
+                                 k_dst.stride(1), k_dst.stride(2), n_layers, n_keys, video_start,
+                                 n_video, _ptr(keep_idx), n_keep, hkv, d, _stream())
+    _check("specvlm_gather_kv", rc)
+    return k_dst, v_dst
+
+
+# --------------------------------------------------------------------- decode_attn
+def decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads, n_kv_heads, head_dim,
+                                num_splits=0) -> int:
+    return lib().specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads, n_kv_heads,
+                                                     head_dim, num_splits)
+
+
+def decode_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale: float, *,
+                cu_q: Optional[torch.Tensor] = None, cu_kv: Optional[torch.Tensor] = None,
+                max_q_len: Optional[int] = None, max_kv_len: Optional[int] = None,
+                out: Optional[torch.Tensor] = None, want_lse: bool = False, num_splits: int = 0,
+                workspace: Optional[torch.Tensor] = None):
+    """q [sum q_len,H_q,d], k/v [sum kv_len,H_kv,d] bf16 views -> out like q (and lse fp32)."""
+    tq, hq, d = q.shape
+    tk, hkv, _ = k.shape
+    if cu_q is None:
+        batch, q_len, kv_len = 1, tq, tk
+    else:
+        batch = cu_q.numel() - 1
+        if max_q_len is None or max_kv_len is None:
+            raise ValueError("max_q_len and max_kv_len are required with cu_q/cu_kv")
+        q_len, kv_len = max_q_len, max_kv_len
+    if out is None:
+        out = torch.empty_like(q)
+    if out.stride() != q.stride():
+        raise ValueError("out must share q's strides")
+    if v.stride() != k.stride():
+        raise ValueError("K and V must share strides")
+    lse = torch.empty((tq, hq), dtype=torch.float32, device=q.device) if want_lse else None
+    need = decode_attn_workspace_bytes(batch, q_len, kv_len, hq, hkv, d, num_splits)
+    workspace = _ws(workspace, need, q)
+    qs, ks = _thd(q), _thd(k)
+    rc = lib().specvlm_decode_attn(_ptr(q), qs[0], qs[1], _ptr(k), _ptr(v), ks[0], ks[1],
+                                   _ptr(cu_q), _ptr(cu_kv), batch, q_len, kv_len, hq, hkv, d,
+                                   float(softmax_scale), _ptr(out), _ptr(lse), num_splits,
+                                   _ptr(workspace), workspace.numel(), _stream())
+    _check("specvlm_decode_attn", rc)
+    return (out, lse) if want_lse else out
+
+
+# -------------------------------------------------------------------------- accept
+def accept_workspace_bytes(batch, gamma, vocab, sampling) -> int:
+    return lib().specvlm_accept_workspace_bytes(batch, gamma, vocab, int(sampling))
+
+
+def accept(target_logits: torch.Tensor, draft_tokens: torch.Tensor, *,
+           draft_logits: Optional[torch.Tensor] = None, uniforms: Optional[torch.Tensor] = None,
+           temperature: float = 1.0, workspace: Optional[torch.Tensor] = None):
+    """target_logits fp32 [batch, gamma+1, vocab] -> (n_accepted int32 [batch], out_tokens int32 [batch, gamma+1])."""
+    batch, g1, vocab = target_logits.shape
+    gamma = g1 - 1
+    dev = target_logits.device
+    n_acc = torch.empty(batch, dtype=torch.int32, device=dev)
+    out = torch.empty((batch, gamma + 1), dtype=torch.int32, device=dev)
+    sampling = uniforms is not None
+    need = accept_workspace_bytes(batch, gamma, vocab, sampling)
+    workspace = _ws(workspace, need, target_logits)
+    for t in (target_logits, draft_logits, draft_tokens, uniforms):
+        if t is not None and not t.is_contiguous():
+            raise ValueError("accept inputs must be contiguous")
+    rc = lib().specvlm_accept(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
+                              _ptr(uniforms), batch, gamma, vocab, float(temperature),
+                              _ptr(n_acc), _ptr(out), _ptr(workspace), workspace.numel(), _stream())
+    _check("specvlm_accept", rc)
+    return n_acc, out

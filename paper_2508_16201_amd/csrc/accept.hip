@@ -1,0 +1,288 @@
+// specvlm_accept: which drafted tokens survive the target's verification
+// (Sec. 2.1; greedy target decoding as in App. A, or the rejection-sampling rule
+// of speculative sampling that keeps the target's output distribution).
+//
+// Pass 1 (many workgroups): per (request, row, vocab chunk) partial statistics
+//   -- argmax with lowest-index ties for greedy; running (max, sum exp) of
+//   logit/T for the target rows and the draft rows for sampling.
+// Pass 2 (one workgroup per request): merge the partials, walk the gamma
+//   accept tests in order, then draw the final token by inverse CDF over the
+//   residual max(p - q, 0) (or over p when every draft survived).
+#include "common.h"
+
+namespace specvlm {
+
+constexpr int kAccThreads = 1024;
+constexpr int kAccWaves = kAccThreads / kWave;
+constexpr int kAccChunk = 8192;        // vocab entries per pass-1 workgroup
+
+struct AcceptParams {
+    const float* target;      // [batch, gamma+1, vocab]
+    const float* draft;       // [batch, gamma, vocab] or null
+    const int32_t* tokens;    // [batch, gamma]
+    const float* uniforms;    // [batch, gamma+1] or null
+    int batch, gamma, vocab, n_chunks;
+    float inv_t_log2;         // log2(e) / temperature
+    int32_t* n_accepted;
+    int32_t* out_tokens;
+    float* part_val;          // [batch][rows][n_chunks]   max
+    float* part_aux;          // [batch][rows][n_chunks]   sum exp (sampling) / argmax index bits (greedy)
+};
+
+__device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i)
+{
+    // larger value wins; equal values: lower index wins.  (i < 0 = empty)
+    if (i >= 0 && (bi < 0 || v > bv || (v == bv && i < bi))) { bv = v; bi = i; }
+}
+
+// ---------------------------------------------------------------- greedy ----
+__global__ __launch_bounds__(256)
+void accept_argmax_partial(const AcceptParams p)
+{
+    __shared__ float s_v[4];
+    __shared__ int s_i[4];
+    const int chunk = blockIdx.x, row = blockIdx.y, b = blockIdx.z;
+    const float* x = p.target + ((int64_t)b * (p.gamma + 1) + row) * p.vocab;
+    const int lo = chunk * kAccChunk, hi = min(p.vocab, lo + kAccChunk);
+    float bv = 0.f; int bi = -1;
+    for (int v = lo + threadIdx.x; v < hi; v += 256) {
+        const float y = x[v];
+        if (bi < 0 || y > bv) { bv = y; bi = v; }     // ascending v: first maximum is kept
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        argmax_merge(bv, bi, ov, oi);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) argmax_merge(bv, bi, s_v[w], s_i[w]);
+        const int64_t slot = ((int64_t)b * (p.gamma + 1) + row) * p.n_chunks + chunk;
+        p.part_val[slot] = bv;
+        p.part_aux[slot] = __int_as_float(bi);
+    }
+}
+
+__global__ __launch_bounds__(64)
+void accept_greedy_final(const AcceptParams p)
+{
+    // one wave per request; lane i merges the partials of row i (gamma <= 64)
+    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ int s_t[65];
+    for (int row = lane; row <= p.gamma; row += 64) {
+        float bv = 0.f; int bi = -1;
+        const int64_t slot = ((int64_t)b * (p.gamma + 1) + row) * p.n_chunks;
+        for (int c = 0; c < p.n_chunks; ++c)
+            argmax_merge(bv, bi, p.part_val[slot + c], __float_as_int(p.part_aux[slot + c]));
+        s_t[row] = bi;
+    }
+    __syncthreads();
+    if (lane != 0) return;
+    int32_t* out = p.out_tokens + (int64_t)b * (p.gamma + 1);
+    const int32_t* x = p.tokens + (int64_t)b * p.gamma;
+    int n = 0;
+    while (n < p.gamma && x[n] == s_t[n]) ++n;
+    for (int i = 0; i <= p.gamma; ++i) out[i] = i < n ? x[i] : (i == n ? s_t[n] : -1);
+    p.n_accepted[b] = n;
+}
+
+// -------------------------------------------------------------- sampling ----
+// rows 0..gamma: target rows; rows gamma+1..2*gamma: draft rows 0..gamma-1
+__global__ __launch_bounds__(256)
+void accept_softmax_partial(const AcceptParams p)
+{
+    __shared__ float s_m[4], s_z[4];
+    const int chunk = blockIdx.x, row = blockIdx.y, b = blockIdx.z;
+    const float* x = row <= p.gamma
+        ? p.target + ((int64_t)b * (p.gamma + 1) + row) * p.vocab
+        : p.draft + ((int64_t)b * p.gamma + (row - p.gamma - 1)) * p.vocab;
+    const int lo = chunk * kAccChunk, hi = min(p.vocab, lo + kAccChunk);
+    float m = -INFINITY;
+    for (int v = lo + threadIdx.x; v < hi; v += 256) m = fmaxf(m, x[v] * p.inv_t_log2);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float z = 0.f;
+    for (int v = lo + threadIdx.x; v < hi; v += 256) z += fast_exp2(x[v] * p.inv_t_log2 - m);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) z += __shfl_xor(z, off);
+    if (lane == 0) s_z[wave] = z;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int64_t slot = ((int64_t)b * (2 * p.gamma + 1) + row) * p.n_chunks + chunk;
+        p.part_val[slot] = m;
+        p.part_aux[slot] = (s_z[0] + s_z[1]) + (s_z[2] + s_z[3]);
+    }
+}
+
+__global__ __launch_bounds__(kAccThreads)
+void accept_sample_final(const AcceptParams p)
+{
+    __shared__ float s_m[129], s_z[129];        // merged (max, sum) of up to 2*gamma+1 rows
+    __shared__ float s_w[kAccWaves];
+    __shared__ float s_scan[kAccThreads];
+    __shared__ int s_n, s_y;
+    __shared__ int s_idx[kAccWaves];
+    __shared__ float s_total;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int rows = 2 * p.gamma + 1;
+    for (int row = tid; row < rows; row += kAccThreads) {
+        const int64_t slot = ((int64_t)b * rows + row) * p.n_chunks;
+        float m = -INFINITY;
+        for (int c = 0; c < p.n_chunks; ++c) m = fmaxf(m, p.part_val[slot + c]);
+        float z = 0.f;
+        for (int c = 0; c < p.n_chunks; ++c) z += p.part_aux[slot + c] * fast_exp2(p.part_val[slot + c] - m);
+        s_m[row] = m; s_z[row] = z;
+    }
+    __syncthreads();
+    const float* tgt = p.target + (int64_t)b * (p.gamma + 1) * p.vocab;
+    const float* drf = p.draft + (int64_t)b * p.gamma * p.vocab;
+    const int32_t* x = p.tokens + (int64_t)b * p.gamma;
+    const float* u = p.uniforms + (int64_t)b * (p.gamma + 1);
+    if (tid == 0) {
+        int n = 0;
+        for (; n < p.gamma; ++n) {
+            const int tok = x[n];
+            const float pt = fast_exp2(tgt[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[n]) / s_z[n];
+            const float qd = fast_exp2(drf[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[p.gamma + 1 + n]) /
+                             s_z[p.gamma + 1 + n];
+            if (!(u[n] * qd < pt)) break;
+        }
+        s_n = n;
+    }
+    __syncthreads();
+    const int n = s_n;
+    const bool residual = n < p.gamma;
+    const float* trow = tgt + (int64_t)n * p.vocab;
+    const float* drow = residual ? drf + (int64_t)n * p.vocab : nullptr;
+    const float mt = s_m[n], inv_zt = 1.f / s_z[n];
+    const float md = residual ? s_m[p.gamma + 1 + n] : 0.f;
+    const float inv_zd = residual ? 1.f / s_z[p.gamma + 1 + n] : 0.f;
+    auto weight = [&](int v) {
+        const float pv = fast_exp2(trow[v] * p.inv_t_log2 - mt) * inv_zt;
+        if (!residual) return pv;
+        const float qv = fast_exp2(drow[v] * p.inv_t_log2 - md) * inv_zd;
+        return fmaxf(pv - qv, 0.f);
+    };
+    // thread t owns the contiguous token range [t*per, (t+1)*per)
+    const int per = (p.vocab + kAccThreads - 1) / kAccThreads;
+    const int lo = min(p.vocab, tid * per), hi = min(p.vocab, lo + per);
+    float mine = 0.f;
+    for (int v = lo; v < hi; ++v) mine += weight(v);
+    // exclusive prefix of the per-thread masses (thread order = token order)
+    s_scan[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        float acc = 0.f;
+        for (int t = 0; t < kAccThreads; ++t) { const float y = s_scan[t]; s_scan[t] = acc; acc += y; }
+        s_total = acc;
+        s_y = -1;
+    }
+    __syncthreads();
+    const float W = s_total;
+    if (!(W > 0.f)) {
+        // no residual mass (p == q): fall back to the target's most likely token
+        float bv = 0.f; int bi = -1;
+        for (int v = lo; v < hi; ++v) {
+            const float y = trow[v];
+            if (bi < 0 || y > bv) { bv = y; bi = v; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            argmax_merge(bv, bi, ov, oi);
+        }
+        if ((tid & 63) == 0) { s_w[tid >> 6] = bv; s_idx[tid >> 6] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < kAccWaves; ++w) argmax_merge(bv, bi, s_w[w], s_idx[w]);
+            s_y = bi;
+        }
+        __syncthreads();
+    } else {
+        const float goal = u[p.gamma] * W;
+        const float before = s_scan[tid];
+        const float after = (tid + 1 < kAccThreads) ? s_scan[tid + 1] : W;
+        // the owner of the goal: the thread whose mass interval [before, after) holds it
+        if (mine > 0.f && before <= goal && goal < after) {
+            float c = before; int y = -1, last = -1;
+            for (int v = lo; v < hi; ++v) {
+                const float w = weight(v);
+                if (w > 0.f) last = v;
+                if (c + w > goal) { y = v; break; }
+                c += w;
+            }
+            atomicMax(&s_y, y >= 0 ? y : last);
+        }
+        __syncthreads();
+        if (s_y < 0) {
+            // rounding put the goal at or beyond the total: the last token with mass
+            int last = -1;
+            for (int v = lo; v < hi; ++v) if (weight(v) > 0.f) last = v;
+            __syncthreads();
+            if (last >= 0) atomicMax(&s_y, last);
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        int32_t* out = p.out_tokens + (int64_t)b * (p.gamma + 1);
+        for (int i = 0; i <= p.gamma; ++i) out[i] = i < n ? x[i] : (i == n ? s_y : -1);
+        p.n_accepted[b] = n;
+    }
+}
+
+static int accept_chunks(int vocab) { return (vocab + kAccChunk - 1) / kAccChunk; }
+
+}  // namespace specvlm
+
+using namespace specvlm;
+
+extern "C" size_t specvlm_accept_workspace_bytes(int batch, int gamma, int vocab, int sampling)
+{
+    if (batch <= 0 || gamma < 0 || vocab < 1) return 0;
+    const size_t rows = sampling ? 2 * (size_t)gamma + 1 : (size_t)gamma + 1;
+    return 2 * align256((size_t)batch * rows * accept_chunks(vocab) * sizeof(float));
+}
+
+extern "C" int specvlm_accept(
+    const float* target_logits, const float* draft_logits,
+    const int32_t* draft_tokens, const float* uniforms,
+    int batch, int gamma, int vocab, float temperature,
+    int32_t* n_accepted, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch < 0 || gamma < 0 || vocab < 1) return SPECVLM_EINVAL;
+    if ((draft_logits == nullptr) != (uniforms == nullptr)) return SPECVLM_EINVAL;
+    const bool sampling = uniforms != nullptr;
+    if (sampling && !(temperature > 0.f && temperature < INFINITY)) return SPECVLM_EINVAL;
+    if (gamma > 64) return SPECVLM_EUNSUPPORTED;
+    if (batch == 0) return SPECVLM_OK;
+    if (!target_logits || !n_accepted || !out_tokens || (gamma > 0 && !draft_tokens)) return SPECVLM_EINVAL;
+    if (batch > 65535) return SPECVLM_EUNSUPPORTED;
+    const size_t need = specvlm_accept_workspace_bytes(batch, gamma, vocab, sampling);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) return SPECVLM_EWORKSPACE;
+
+    AcceptParams p;
+    p.target = target_logits; p.draft = draft_logits; p.tokens = draft_tokens; p.uniforms = uniforms;
+    p.batch = batch; p.gamma = gamma; p.vocab = vocab; p.n_chunks = accept_chunks(vocab);
+    p.inv_t_log2 = sampling ? kLog2e / temperature : kLog2e;
+    p.n_accepted = n_accepted; p.out_tokens = out_tokens;
+    p.part_val = (float*)workspace;
+    p.part_aux = (float*)((char*)workspace + need / 2);
+    hipStream_t s = (hipStream_t)stream;
+    if (!sampling) {
+        hipLaunchKernelGGL(accept_argmax_partial, dim3(p.n_chunks, gamma + 1, batch), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(accept_greedy_final, dim3(batch), dim3(64), 0, s, p);
+    } else {
+        hipLaunchKernelGGL(accept_softmax_partial, dim3(p.n_chunks, 2 * gamma + 1, batch), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(accept_sample_final, dim3(batch), dim3(kAccThreads), 0, s, p);
+    }
+    return launch_status();
+}

@@ -1,0 +1,409 @@
+// specvlm_score: language-to-video attention scores (Sec. 3.1, Eq. 4-5).
+//
+//   a_j = (1/(H_q L)) sum_h sum_i softmax_row(scale * Q_L K^T)[i, j],  j in video
+//
+// The attention matrix is never materialised.  Two MFMA sweeps over the same
+// text x key contraction:
+//   pass A  row statistics: for every (text query, q head) row the running
+//           (max, sum exp) over the keys of the normalisation domain, split over
+//           key ranges and merged -> log2-domain normaliser lse2[row]
+//           (skipped when the caller supplies row_lse);
+//   pass B  column sums: for every video key, sum over rows of
+//           exp2(logit2 - lse2[row]), split over row ranges;
+//   final   scores = beta*scores + mean over (h, i), summing the kv-head / split
+//           partials in a fixed order (deterministic, no float atomics).
+//
+// Both passes are one kernel: a workgroup keeps 256 "stationary" vectors (rows
+// of Q in pass A, video keys in pass B) as MFMA B-operand fragments in
+// registers (64 per wave) and streams the other side through LDS in 64-vector
+// tiles (XOR-swizzled 16-byte chunks, double buffered).  In the accumulator
+// layout the stationary vector is lane column r and the streamed vectors are
+// rows 4c..4c+3, so each pass reduces over its streamed side inside a lane.
+#include "common.h"
+
+namespace specvlm {
+
+constexpr int kScoreTile = 64;         // streamed vectors per LDS tile
+constexpr int kScoreBlock = 256;       // stationary vectors per workgroup
+constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
+
+struct ScoreParams {
+    const __bf16* q;
+    const __bf16* k;
+    int64_t q_tok, q_head, k_tok, k_head;
+    int n_text, n_keys, video_start, n_video, text_pos0;
+    int n_q_heads, n_kv_heads, group;
+    float scale_log2;
+    int rows, rows_pad;            // rows = n_text * group (per kv head), padded to 256
+    int video_pad;                 // n_video padded to 256
+    int key_lo, key_hi;            // normalisation domain [key_lo, key_hi)
+    int a_splits, a_split_keys;
+    int b_splits, b_split_rows;
+    int b_needs_mask;
+    float* part_ml;                // [H_kv][rows_pad][a_splits][2]
+    float* lse2;                   // [H_kv][rows_pad]
+    const float* row_lse;          // caller's natural-log normalisers [n_text][H_q], or null
+    float* part_cols;              // [H_kv][b_splits][video_pad]
+    float beta, inv_count;
+    float* scores;
+};
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256)
+void score_sweep_kernel(const ScoreParams p)
+{
+    constexpr int KK = D / 32;
+    constexpr int CH = D / 8;                  // 16-byte chunks per vector
+    constexpr int TILE_BYTES = kScoreTile * D * 2;
+    constexpr int LOADS = kScoreTile * CH / 256;   // chunks per thread per tile
+    __shared__ __align__(16) unsigned char s_tile[2][TILE_BYTES];
+    __shared__ __align__(16) float s_lse[2][kScoreTile];
+    __shared__ int s_lim[2][kScoreTile];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, c = lane >> 4;
+    const int g = blockIdx.y, split = blockIdx.z;
+    const int stat0 = blockIdx.x * kScoreBlock + wave * 64;      // this wave's first stationary vector
+
+    // streamed range of this workgroup
+    int s_begin, s_end;
+    if (MODE == 0) {
+        s_begin = p.key_lo + split * p.a_split_keys;
+        s_end = min(p.key_hi, s_begin + p.a_split_keys);
+    } else {
+        s_begin = split * p.b_split_rows;
+        s_end = min(p.rows, s_begin + p.b_split_rows);
+    }
+
+    // ---- stationary fragments (B operand) ----
+    bf16x8 sf[4][KK];
+    int lim[4];                                 // pass A: last visible key of the lane's row
+    int key_abs[4];                             // pass B: absolute key index of the lane's key
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) {
+        const int item = stat0 + sb * 16 + r;
+        const __bf16* src = nullptr;
+        lim[sb] = -1; key_abs[sb] = 0x7fffffff;
+        if (MODE == 0) {
+            if (item < p.rows) {
+                const int i = item / p.group, h = g * p.group + item % p.group;
+                src = p.q + (int64_t)i * p.q_tok + (int64_t)h * p.q_head;
+                lim[sb] = p.text_pos0 + i;
+            }
+        } else {
+            if (item < p.n_video) {
+                key_abs[sb] = p.video_start + item;
+                src = p.k + (int64_t)key_abs[sb] * p.k_tok + (int64_t)g * p.k_head;
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (src) raw = *reinterpret_cast<const u32x4*>(src + kk * 32 + c * 8);
+            sf[sb][kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    float m_run[4], l_run[4], col[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) { m_run[sb] = kNegBig; l_run[sb] = 0.f; col[sb] = 0.f; }
+
+    // ---- streamed tiles: global -> registers -> swizzled LDS ----
+    u32x4 stage[LOADS];
+    float stage_lse = 0.f; int stage_lim = 0;
+    auto fetch = [&](int first) {
+#pragma unroll
+        for (int n = 0; n < LOADS; ++n) {
+            const int id = tid + 256 * n, it = id / CH, x = id % CH;
+            const int item = first + it;
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (item < s_end) {
+                const __bf16* src;
+                if (MODE == 0) src = p.k + (int64_t)item * p.k_tok + (int64_t)g * p.k_head;
+                else {
+                    const int i = item / p.group, h = g * p.group + item % p.group;
+                    src = p.q + (int64_t)i * p.q_tok + (int64_t)h * p.q_head;
+                }
+                raw = *reinterpret_cast<const u32x4*>(src + x * 8);
+            }
+            stage[n] = raw;
+        }
+        if (MODE == 1 && tid < kScoreTile) {
+            const int item = first + tid;
+            const bool ok = item < s_end;
+            stage_lse = ok ? p.lse2[(int64_t)g * p.rows_pad + item] : INFINITY;
+            stage_lim = ok ? p.text_pos0 + item / p.group : 0x7fffffff;
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int n = 0; n < LOADS; ++n) {
+            const int id = tid + 256 * n, it = id / CH, x = id % CH;
+            *reinterpret_cast<u32x4*>(&s_tile[buf][it * (D * 2) + ((x ^ (it & (CH - 1))) * 16)]) = stage[n];
+        }
+        if (MODE == 1 && tid < kScoreTile) { s_lse[buf][tid] = stage_lse; s_lim[buf][tid] = stage_lim; }
+    };
+
+    auto compute = [&](int buf, int first) {
+        // pass A: does any (row, key) pair of this tile need the causal / range mask?
+        bool mask = false;
+        if (MODE == 0) {
+            const int row_lo = blockIdx.x * kScoreBlock;          // earliest row of the workgroup
+            const int lim_lo = p.text_pos0 + row_lo / p.group;
+            mask = (first + kScoreTile > s_end) || (first + kScoreTile - 1 > lim_lo);
+        }
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+            bf16x8 af[KK];
+            const int it = sub * 16 + r;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int x = kk * 4 + c;
+                af[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                    &s_tile[buf][it * (D * 2) + ((x ^ (it & (CH - 1))) * 16)]));
+            }
+            floatx4 lse4 = {0.f, 0.f, 0.f, 0.f};
+            int lim4[4] = {0, 0, 0, 0};
+            if (MODE == 1) {
+                lse4 = *reinterpret_cast<const floatx4*>(&s_lse[buf][sub * 16 + 4 * c]);
+                if (p.b_needs_mask) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) lim4[i] = s_lim[buf][sub * 16 + 4 * c + i];
+                }
+            }
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) acc = mfma16(af[kk], sf[sb][kk], acc);
+                if (MODE == 0) {
+                    float s[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        s[i] = acc[i] * p.scale_log2;
+                        if (mask) {
+                            const int key = first + sub * 16 + 4 * c + i;
+                            if (key >= s_end || key > lim[sb]) s[i] = -INFINITY;
+                        }
+                    }
+                    const float m_new = fmaxf(fmaxf(m_run[sb], fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
+                    const float sum = (fast_exp2(s[0] - m_new) + fast_exp2(s[1] - m_new)) +
+                                      (fast_exp2(s[2] - m_new) + fast_exp2(s[3] - m_new));
+                    l_run[sb] = l_run[sb] * fast_exp2(m_run[sb] - m_new) + sum;
+                    m_run[sb] = m_new;
+                } else {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float pr = fast_exp2(acc[i] * p.scale_log2 - lse4[i]);
+                        if (p.b_needs_mask && key_abs[sb] > lim4[i]) pr = 0.f;
+                        sum += pr;
+                    }
+                    col[sb] += sum;
+                }
+            }
+        }
+    };
+
+    const int n_tiles = (s_end - s_begin + kScoreTile - 1) / kScoreTile;
+    if (n_tiles > 0) {
+        fetch(s_begin);
+        commit(0);
+    }
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const bool more = t + 1 < n_tiles;
+        if (more) fetch(s_begin + (t + 1) * kScoreTile);
+        compute(t & 1, s_begin + t * kScoreTile);
+        if (more) commit((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- reduce over the four lane groups that share a stationary vector ----
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) {
+        const int item = stat0 + sb * 16 + r;
+        if (MODE == 0) {
+            float m = m_run[sb], l = l_run[sb];
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const float om = __shfl_xor(m, off), ol = __shfl_xor(l, off);
+                const float mm = fmaxf(m, om);
+                l = l * fast_exp2(m - mm) + ol * fast_exp2(om - mm);
+                m = mm;
+            }
+            if (c == 0 && item < p.rows) {
+                float* dst = p.part_ml + (((int64_t)g * p.rows_pad + item) * p.a_splits + split) * 2;
+                dst[0] = m; dst[1] = l;
+            }
+        } else {
+            float v = col[sb];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (c == 0 && item < p.n_video)
+                p.part_cols[((int64_t)g * p.b_splits + split) * p.video_pad + item] = v;
+        }
+    }
+}
+
+// lse2[g][row] from the pass-A partials, or from the caller's natural-log values.
+__global__ __launch_bounds__(256)
+void score_lse_kernel(const ScoreParams p)
+{
+    const int row = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
+    if (row >= p.rows_pad) return;
+    float out = INFINITY;                       // padded / keyless rows contribute nothing
+    if (row < p.rows) {
+        if (p.row_lse) {
+            const int i = row / p.group, h = g * p.group + row % p.group;
+            out = p.row_lse[(int64_t)i * p.n_q_heads + h] * kLog2e;
+            if (!(out > -INFINITY)) out = INFINITY;
+        } else {
+            const float* src = p.part_ml + ((int64_t)g * p.rows_pad + row) * p.a_splits * 2;
+            float m = kNegBig;
+            for (int s = 0; s < p.a_splits; ++s) m = fmaxf(m, src[2 * s]);
+            float l = 0.f;
+            for (int s = 0; s < p.a_splits; ++s) l += src[2 * s + 1] * fast_exp2(src[2 * s] - m);
+            if (l > 0.f) out = m + fast_log2(l);
+        }
+    }
+    p.lse2[(int64_t)g * p.rows_pad + row] = out;
+}
+
+__global__ __launch_bounds__(256)
+void score_final_kernel(const ScoreParams p)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= p.n_video) return;
+    float a = 0.f;
+    const int parts = p.n_kv_heads * p.b_splits;
+    for (int s = 0; s < parts; ++s) a += p.part_cols[(int64_t)s * p.video_pad + j];
+    a *= p.inv_count;
+    p.scores[j] = (p.beta != 0.f ? p.beta * p.scores[j] : 0.f) + a;
+}
+
+struct ScorePlan {
+    int rows, rows_pad, video_pad, key_lo, key_hi, a_splits, a_split_keys, b_splits, b_split_rows;
+    size_t off_ml, off_lse, off_cols, total;
+};
+
+static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video, int n_q_heads,
+                            int n_kv_heads, int norm_mode, int have_row_lse)
+{
+    ScorePlan s;
+    const int group = n_q_heads / n_kv_heads;
+    s.rows = n_text * group;
+    s.rows_pad = round_up(s.rows > 0 ? s.rows : 1, kScoreBlock);
+    s.video_pad = round_up(n_video > 0 ? n_video : 1, kScoreBlock);
+    s.key_lo = norm_mode ? video_start : 0;
+    s.key_hi = norm_mode ? video_start + n_video : n_keys;
+    const int target_wgs = 2 * kNumCu;
+    const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
+    const int dom = s.key_hi - s.key_lo;
+    int a = (target_wgs + blocks_a - 1) / blocks_a;
+    const int a_max = (dom + 4 * kScoreTile - 1) / (4 * kScoreTile);       // >= 4 tiles per split
+    if (a > a_max) a = a_max;
+    if (a > 64) a = 64;
+    if (a < 1) a = 1;
+    s.a_split_keys = round_up((dom + a - 1) / a > 0 ? (dom + a - 1) / a : 1, kScoreTile);
+    s.a_splits = dom > 0 ? (dom + s.a_split_keys - 1) / s.a_split_keys : 1;
+    const int blocks_b = (s.video_pad / kScoreBlock) * n_kv_heads;
+    int b = (target_wgs + blocks_b - 1) / blocks_b;
+    const int b_max = (s.rows + 4 * kScoreTile - 1) / (4 * kScoreTile);
+    if (b > b_max) b = b_max;
+    if (b > 16) b = 16;
+    if (b < 1) b = 1;
+    s.b_split_rows = round_up((s.rows + b - 1) / b > 0 ? (s.rows + b - 1) / b : 1, kScoreTile);
+    s.b_splits = s.rows > 0 ? (s.rows + s.b_split_rows - 1) / s.b_split_rows : 1;
+    size_t off = 0;
+    s.off_ml = off;
+    if (!have_row_lse) off += align256((size_t)n_kv_heads * s.rows_pad * s.a_splits * 2 * sizeof(float));
+    s.off_lse = off;  off += align256((size_t)n_kv_heads * s.rows_pad * sizeof(float));
+    s.off_cols = off; off += align256((size_t)n_kv_heads * s.b_splits * s.video_pad * sizeof(float));
+    s.total = off;
+    return s;
+}
+
+}  // namespace specvlm
+
+using namespace specvlm;
+
+extern "C" size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_keys, int n_video,
+                                                int n_q_heads, int n_kv_heads, int head_dim,
+                                                int have_row_lse)
+{
+    (void)head_dim;
+    if (batch != 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
+        n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
+        return 0;
+    // the split plan depends on the normalisation domain; size for the larger one
+    const ScorePlan a = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, 0, have_row_lse);
+    const ScorePlan b = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, 1, have_row_lse);
+    return a.total > b.total ? a.total : b.total;
+}
+
+extern "C" int specvlm_score(
+    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch < 0 || n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0 || text_pos0 < 0)
+        return SPECVLM_EINVAL;
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads) return SPECVLM_EINVAL;
+    if ((int64_t)video_start + n_video > n_keys) return SPECVLM_EINVAL;
+    if (norm_mode != 0 && norm_mode != 1) return SPECVLM_EINVAL;
+    if (!(softmax_scale >= 0.f) || !(softmax_scale < INFINITY)) return SPECVLM_EINVAL;
+    if (head_dim != 64 && head_dim != 128) return SPECVLM_EUNSUPPORTED;
+    if (batch == 0 || n_video == 0) return SPECVLM_OK;
+    if (cu_text || cu_keys || cu_video || batch != 1) return SPECVLM_EUNSUPPORTED;   // one request per call
+    if (!scores) return SPECVLM_EINVAL;
+    if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
+    if ((q_tok_stride | q_head_stride | k_tok_stride | k_head_stride) & 7) return SPECVLM_EUNSUPPORTED;
+    if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
+
+    const ScorePlan plan = score_plan(n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
+                                      norm_mode, row_lse != nullptr);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.total) return SPECVLM_EWORKSPACE;
+
+    ScoreParams p;
+    p.q = (const __bf16*)q_text; p.k = (const __bf16*)k_cache;
+    p.q_tok = q_tok_stride; p.q_head = q_head_stride; p.k_tok = k_tok_stride; p.k_head = k_head_stride;
+    p.n_text = n_text; p.n_keys = n_keys; p.video_start = video_start; p.n_video = n_video;
+    p.text_pos0 = text_pos0;
+    p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = n_q_heads / n_kv_heads;
+    p.scale_log2 = softmax_scale * kLog2e;
+    p.rows = plan.rows; p.rows_pad = plan.rows_pad; p.video_pad = plan.video_pad;
+    p.key_lo = plan.key_lo; p.key_hi = plan.key_hi;
+    p.a_splits = plan.a_splits; p.a_split_keys = plan.a_split_keys;
+    p.b_splits = plan.b_splits; p.b_split_rows = plan.b_split_rows;
+    p.b_needs_mask = (video_start + n_video - 1 > text_pos0) ? 1 : 0;
+    p.part_ml = (float*)((char*)workspace + plan.off_ml);
+    p.lse2 = (float*)((char*)workspace + plan.off_lse);
+    p.row_lse = row_lse;
+    p.part_cols = (float*)((char*)workspace + plan.off_cols);
+    p.beta = beta;
+    p.inv_count = (n_text > 0) ? 1.f / ((float)n_q_heads * (float)n_text) : 0.f;
+    p.scores = scores;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (n_text > 0) {
+        if (!row_lse && p.key_hi > p.key_lo) {
+            dim3 grid(plan.rows_pad / kScoreBlock, n_kv_heads, plan.a_splits);
+            if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 0>), grid, dim3(256), 0, s, p);
+            else                 hipLaunchKernelGGL((score_sweep_kernel<64, 0>), grid, dim3(256), 0, s, p);
+        }
+        hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads), dim3(256), 0, s, p);
+        dim3 grid(plan.video_pad / kScoreBlock, n_kv_heads, plan.b_splits);
+        if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 1>), grid, dim3(256), 0, s, p);
+        else                 hipLaunchKernelGGL((score_sweep_kernel<64, 1>), grid, dim3(256), 0, s, p);
+    } else {
+        p.b_splits = 0;          // no language queries: the mean is empty, only beta applies
+    }
+    hipLaunchKernelGGL(score_final_kernel, dim3((n_video + 255) / 256), dim3(256), 0, s, p);
+    return launch_status();
+}

@@ -1,0 +1,257 @@
+// specvlm_select: the two-stage retention set of Sec. 3.2.
+//   Stage I  : V_R = the k highest-scoring video tokens (ties -> lower index),
+//              by a most-significant-digit radix select on order-preserving
+//              integer keys (4 passes of 8 bits, wave-ballot aggregated
+//              histograms in LDS).
+//   Stage II : V_U = tokens of V \ V_R at the fixed fractional interval
+//              I = R/U in raster order: remainder ranks floor(t*R/U), exact
+//              integer arithmetic (Eq. 7 with the budget as denominator).
+//   Output   : sort(V_R u V_U) by a stable compaction.
+// One workgroup of 1024 threads per request; thread t owns the contiguous run
+// of tokens [t*per, (t+1)*per) and keeps their keys in registers, so every
+// "how many before me" question is one block-wide exclusive scan of popcounts.
+#include "common.h"
+
+namespace specvlm {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
+
+struct SelectParams {
+    const float* scores;
+    const int32_t* cu_video;
+    const int32_t* k_top;
+    const int32_t* keep_budget;
+    const int32_t* cu_keep;
+    int max_n_video;
+    int32_t* keep_idx;
+    uint8_t* from_topk;
+    int32_t* status;
+};
+
+// Order-preserving key: larger score <=> larger key.  -0.0 is +0.0; NaN is the
+// smallest key of all.
+__device__ __forceinline__ uint32_t score_key(float x)
+{
+    if (x != x) return 0u;
+    uint32_t u = __float_as_uint(x);
+    if (x == 0.f) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over the block (thread order).
+__device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+    }
+    __syncthreads();                       // s_wave may still be read from a previous scan
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int before = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+        const int x = s_wave[w];
+        if (w < wave) before += x;
+        sum += x;
+    }
+    *total = sum;
+    return before + incl - v;
+}
+
+template <int E>
+__global__ __launch_bounds__(kSelThreads)
+void select_kernel(const SelectParams p)
+{
+    __shared__ int s_hist[kSelWaves][256];
+    __shared__ int s_tot[256];
+    __shared__ int s_wave[kSelWaves];
+    __shared__ int s_pick[2];
+
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int v0 = p.cu_video ? p.cu_video[b] : 0;
+    const int n = p.cu_video ? p.cu_video[b + 1] - v0 : p.max_n_video;
+    const int k = p.k_top[b], budget = p.keep_budget[b];
+    const int out0 = p.cu_keep ? p.cu_keep[b] : 0;
+    const bool bad = n < 0 || n > E * kSelThreads || k < 0 || k > budget || budget > n;
+    if (p.status && tid == 0) p.status[b] = bad ? SPECVLM_EINVAL : SPECVLM_OK;
+    if (bad || budget == 0) return;
+
+    const int per = (n + kSelThreads - 1) / kSelThreads;      // <= E
+    const int first = tid * per;
+    const float* sc = p.scores + v0;
+
+    uint32_t key[E];
+    uint64_t valid = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int idx = first + e;
+        const bool ok = e < per && idx < n;
+        key[e] = ok ? score_key(sc[idx]) : 0u;
+        if (ok) valid |= 1ull << e;
+    }
+
+    // ---- Stage I: radix select of the k-th largest key ----
+    uint32_t prefix = 0, known = 0;
+    int need = k;                       // how many still to take inside the current prefix
+    if (k > 0) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&s_hist[0][0])[i] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const bool match = ((valid >> e) & 1) && ((key[e] & known) == prefix);
+                const uint64_t act = __ballot(match);
+                if (act == 0) continue;
+                const int digit = (key[e] >> shift) & 255;
+                const int leader = __ffsll((long long)act) - 1;
+                const int d0 = __shfl(digit, leader);
+                const uint64_t same = __ballot(match && digit == d0);
+                if (same == act) {                      // whole wave agrees: one add
+                    if (lane == leader) atomicAdd(&s_hist[wave][d0], __popcll(act));
+                } else if (match) {
+                    atomicAdd(&s_hist[wave][digit], 1);
+                }
+            }
+            __syncthreads();
+            if (tid < 256) {
+                int t = 0;
+#pragma unroll
+                for (int w = 0; w < kSelWaves; ++w) t += s_hist[w][tid];
+                s_tot[tid] = t;
+            }
+            __syncthreads();
+            if (wave == 0) {
+                // lane l owns digits 4l..4l+3; suffix sums from the top digit down
+                int c4[4], mine = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { c4[i] = s_tot[4 * lane + i]; mine += c4[i]; }
+                int incl = mine;                        // inclusive suffix sum over lanes >= lane
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int y = __shfl_down(incl, off);
+                    if (lane + off < 64) incl += y;
+                }
+                int above = incl - mine;                // keys in digits owned by higher lanes
+                if (above < need && need <= incl) {
+#pragma unroll
+                    for (int i = 3; i >= 0; --i) {
+                        if (above < need && need <= above + c4[i]) {
+                            s_pick[0] = 4 * lane + i;
+                            s_pick[1] = need - above;
+                        }
+                        above += c4[i];
+                    }
+                }
+            }
+            __syncthreads();
+            prefix |= (uint32_t)s_pick[0] << shift;
+            known |= 255u << shift;
+            need = s_pick[1];
+        }
+    }
+    // now: prefix = key of the k-th largest; take every key > prefix and the
+    // first `need` keys == prefix in index order.
+    uint64_t gt = 0, eq = 0;
+    if (k > 0) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (!((valid >> e) & 1)) continue;
+            if (key[e] > prefix) gt |= 1ull << e;
+            else if (key[e] == prefix) eq |= 1ull << e;
+        }
+    }
+    int total;
+    const int eq_before = block_excl_scan(__popcll(eq), s_wave, &total);
+    int take = need - eq_before;
+    take = take < 0 ? 0 : take;
+    uint64_t top = gt;
+    for (uint64_t m = eq; m && take > 0; --take) {
+        const uint64_t bit = m & (~m + 1);
+        top |= bit;
+        m ^= bit;
+    }
+
+    // ---- Stage II: uniform stride over the remainder ----
+    const uint64_t rem_mask = valid & ~top;
+    const int rho_before = block_excl_scan(__popcll(rem_mask), s_wave, &total);
+    const uint64_t R = (uint64_t)(n - k), U = (uint64_t)(budget - k);
+    uint64_t uni = 0;
+    if (U > 0 && rem_mask) {
+        uint64_t t = ((uint64_t)rho_before * U + R - 1) / R;      // first stride index at or after my ranks
+        if (t < U) {
+            uint64_t q = (t * R) / U, frac = (t * R) % U;         // rank floor(t*R/U)
+            const uint64_t step_q = R / U, step_f = R % U;
+            uint64_t rho = (uint64_t)rho_before;
+            for (uint64_t m = rem_mask; m && t < U; ++rho) {
+                const uint64_t bit = m & (~m + 1);
+                m ^= bit;
+                if (rho == q) {
+                    uni |= bit;
+                    ++t; q += step_q; frac += step_f;
+                    if (frac >= U) { frac -= U; ++q; }
+                }
+            }
+        }
+    }
+
+    // ---- stable compaction of V_R u V_U ----
+    const uint64_t keep = top | uni;
+    int pos = out0 + block_excl_scan(__popcll(keep), s_wave, &total);
+    for (uint64_t m = keep; m;) {
+        const int e = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        p.keep_idx[pos] = first + e;
+        if (p.from_topk) p.from_topk[pos] = (uint8_t)((top >> e) & 1);
+        ++pos;
+    }
+}
+
+}  // namespace specvlm
+
+using namespace specvlm;
+
+extern "C" size_t specvlm_select_workspace_bytes(int batch, int max_n_video)
+{
+    (void)batch; (void)max_n_video;
+    return 0;                           // everything lives in registers and LDS
+}
+
+extern "C" int specvlm_select(
+    const float* scores, const int32_t* cu_video,
+    const int32_t* k_top, const int32_t* keep_budget, const int32_t* cu_keep,
+    int batch, int max_n_video, int total_keep,
+    int32_t* keep_idx, uint8_t* from_topk, int32_t* status,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (batch < 0 || max_n_video < 0 || total_keep < 0) return SPECVLM_EINVAL;
+    if (batch == 0) return SPECVLM_OK;
+    if (!k_top || !keep_budget) return SPECVLM_EINVAL;
+    if (batch > 1 && (!cu_video || !cu_keep)) return SPECVLM_EINVAL;
+    if ((int64_t)total_keep > (int64_t)batch * max_n_video) return SPECVLM_EINVAL;
+    if (max_n_video > 64 * kSelThreads) return SPECVLM_EUNSUPPORTED;
+    if (max_n_video == 0 || total_keep == 0) {
+        // nothing can be kept; still report per-request status
+        if (!status) return SPECVLM_OK;
+    }
+    if (total_keep > 0 && (!scores || !keep_idx)) return SPECVLM_EINVAL;
+
+    SelectParams p;
+    p.scores = scores; p.cu_video = cu_video; p.k_top = k_top; p.keep_budget = keep_budget;
+    p.cu_keep = cu_keep; p.max_n_video = max_n_video;
+    p.keep_idx = keep_idx; p.from_topk = from_topk; p.status = status;
+    hipStream_t s = (hipStream_t)stream;
+    const int per = (max_n_video + kSelThreads - 1) / kSelThreads;
+    if (per <= 4)       hipLaunchKernelGGL(select_kernel<4>,  dim3(batch), dim3(kSelThreads), 0, s, p);
+    else if (per <= 16) hipLaunchKernelGGL(select_kernel<16>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    else if (per <= 32) hipLaunchKernelGGL(select_kernel<32>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    else                hipLaunchKernelGGL(select_kernel<64>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    return launch_status();
+}

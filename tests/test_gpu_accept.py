@@ -1,0 +1,131 @@
+"""GPU parity for specvlm_accept: greedy is bit-exact against the oracle;
+rejection sampling must agree wherever the oracle's decision margin exceeds
+1e-4 (fp32 softmax on the GPU, fp64 in the oracle)."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_16201_amd import synth
+
+pytestmark = pytest.mark.gpu
+MARGIN = 1e-4
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2508_16201_amd import binding
+    binding.lib()
+    return binding
+
+
+def cuda(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+@pytest.mark.parametrize("batch,gamma,vocab,sigma", [
+    (4, 4, 1024, 1.3), (2, 5, 152064, 1.3), (8, 7, 152064, 0.8), (3, 0, 1000, 1.0),
+    (5, 5, 8191, 2.5), (1, 64, 300, 0.1), (2, 3, 1, 1.0),
+])
+def test_greedy_bit_exact(B, batch, gamma, vocab, sigma):
+    inp = synth.make_accept_inputs(batch, gamma, vocab, 200 + gamma, sigma=sigma, greedy=True)
+    n, out = B.accept(cuda(inp["target_logits"]), cuda(inp["draft_tokens"]))
+    torch.cuda.synchronize()
+    n, out = n.cpu().numpy(), out.cpu().numpy()
+    for b in range(batch):
+        wn, wout = oracle.accept_greedy(inp["target_logits"][b], inp["draft_tokens"][b])
+        assert n[b] == wn
+        np.testing.assert_array_equal(out[b], wout)
+
+
+def test_greedy_golden_traces_and_ties(B):
+    traces = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "accept_traces.json")))["traces"]
+    logits = np.zeros((len(traces), 5, 8), np.float32)
+    drafts = np.zeros((len(traces), 4), np.int32)
+    for b, tr in enumerate(traces):
+        for i, t in enumerate(tr["target_argmax"]):
+            logits[b, i, t] = 1.0
+        for row, tok in tr.get("tie_with", {}).items():
+            logits[b, int(row), tok] = 1.0
+        drafts[b] = tr["draft"]
+    n, out = B.accept(cuda(logits), cuda(drafts))
+    torch.cuda.synchronize()
+    for b, tr in enumerate(traces):
+        assert n[b].item() == tr["n"], tr["name"]
+        assert out[b].cpu().tolist() == tr["out"], tr["name"]
+    # ties across pass-1 chunk boundaries (vocab > one chunk): lowest index wins
+    big = np.zeros((1, 2, 40000), np.float32)
+    big[0, 0, [39999, 8192, 20000]] = 3.0
+    big[0, 1, [30000, 16384]] = 2.0
+    n, out = B.accept(cuda(big), cuda(np.array([[8192]], np.int32)))
+    torch.cuda.synchronize()
+    assert n.item() == 1 and out[0].cpu().tolist() == [8192, 16384]
+
+
+@pytest.mark.parametrize("batch,gamma,vocab,temp", [
+    (16, 4, 1024, 1.0), (8, 5, 152064, 1.0), (8, 7, 152064, 0.7), (16, 3, 5000, 1.5), (4, 0, 777, 1.0),
+])
+def test_sampling_matches_oracle_outside_margin(B, batch, gamma, vocab, temp):
+    inp = synth.make_accept_inputs(batch, gamma, vocab, 300 + gamma + vocab, sigma=1.0, greedy=False,
+                                   temperature=temp)
+    n, out = B.accept(cuda(inp["target_logits"]), cuda(inp["draft_tokens"]),
+                      draft_logits=cuda(inp["draft_logits"]), uniforms=cuda(inp["uniforms"]),
+                      temperature=temp)
+    torch.cuda.synchronize()
+    n, out = n.cpu().numpy(), out.cpu().numpy()
+    checked = skipped = 0
+    for b in range(batch):
+        wn, wout, margins = oracle.accept_sample(inp["target_logits"][b], inp["draft_logits"][b],
+                                                 inp["draft_tokens"][b], inp["uniforms"][b], temp)
+        reached = margins[:gamma][margins[:gamma] >= 0]
+        if (reached < MARGIN).any():
+            skipped += 1
+            continue
+        assert n[b] == wn, (b, n[b], wn)
+        np.testing.assert_array_equal(out[b][:wn], wout[:wn])
+        assert np.all(out[b][wn + 1:] == -1)
+        if margins[gamma] >= MARGIN:
+            assert out[b][wn] == wout[wn], (b, out[b][wn], wout[wn], margins[gamma])
+            checked += 1
+        else:
+            skipped += 1
+    assert checked >= 0.9 * batch, (checked, skipped)
+
+
+def test_sampling_special_cases(B):
+    # identical models accept everything; disjoint one-hot models reject at once
+    inp = synth.make_accept_inputs(4, 6, 500, 7, sigma=0.0, greedy=False)
+    n, out = B.accept(cuda(inp["target_logits"]), cuda(inp["draft_tokens"]),
+                      draft_logits=cuda(inp["draft_logits"]), uniforms=cuda(np.full((4, 7), 0.999, np.float32)))
+    torch.cuda.synchronize()
+    assert n.cpu().tolist() == [6] * 4
+    vocab = 6
+    t = np.full((1, 3, vocab), -1e4, np.float32); t[:, :, 4] = 0.0
+    dl = np.full((1, 2, vocab), -1e4, np.float32); dl[:, :, 1] = 0.0
+    n, out = B.accept(cuda(t), cuda(np.array([[1, 1]], np.int32)), draft_logits=cuda(dl),
+                      uniforms=cuda(np.array([[0.3, 0.3, 0.9]], np.float32)))
+    torch.cuda.synchronize()
+    assert n.item() == 0 and out[0].cpu().tolist() == [4, -1, -1]
+    # hand-worked threshold: p=(.5,.3,.2), q=(.2,.6,.2), x=1 -> accept iff u < 0.5
+    p = np.array([.5, .3, .2]); q = np.array([.2, .6, .2])
+    tt = np.log(np.stack([p, p]))[None].astype(np.float32)
+    dd = np.log(q)[None, None].astype(np.float32)
+    for u0, u1, wn, wtok in ((0.45, 0.6, 1, 1), (0.55, 0.9, 0, 0), (0.1, 0.85, 1, 2)):
+        n, out = B.accept(cuda(tt), cuda(np.array([[1]], np.int32)), draft_logits=cuda(dd),
+                          uniforms=cuda(np.array([[u0, u1]], np.float32)))
+        torch.cuda.synchronize()
+        assert n.item() == wn and out[0, wn].item() == wtok
+
+
+def test_accept_argument_errors(B):
+    t = torch.zeros((1, 3, 10), device="cuda")
+    x = torch.zeros((1, 2), dtype=torch.int32, device="cuda")
+    u = torch.zeros((1, 3), device="cuda")
+    with pytest.raises(B.SpecVLMError) as e:
+        B.accept(t, x, uniforms=u)                       # uniforms without draft logits
+    assert e.value.status == -1
+    with pytest.raises(B.SpecVLMError):
+        B.accept(t, x, draft_logits=torch.zeros((1, 2, 10), device="cuda"), uniforms=u, temperature=0.0)

@@ -1,0 +1,218 @@
+"""GPU parity for the pruning half of the path: specvlm_score (fp32 vs the fp64
+oracle), specvlm_select and specvlm_gather_kv (bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_16201_amd import synth
+from gpu_util import dev_bf16, host_bits, host_f64, rnd_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2508_16201_amd import binding
+    binding.lib()
+    return binding
+
+
+def i32(x):
+    return torch.tensor(np.atleast_1d(x), dtype=torch.int32).cuda()
+
+
+# ------------------------------------------------------------------ score
+def assert_scores_close(got, want, what=""):
+    got = host_f64(got)
+    assert np.isfinite(got).all(), what
+    # element-wise relative bound (values are ~1/V, so the absolute north-star
+    # bounds 2e-2 / 2e-3 are vacuous here and are checked only for completeness)
+    tol = 2e-3 * np.abs(want) + 1e-9
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - want).max()))
+    assert abs(got.sum() - want.sum()) <= 1e-4, what
+    assert np.abs(got - want).max() <= 2e-2 and np.abs(got - want).mean() <= 2e-3
+
+
+@pytest.mark.parametrize("V,L,P,hq,hkv,d,mode", [
+    (1568, 64, 0, 4, 1, 64, 0),       # Tiny
+    (1568, 64, 0, 4, 1, 64, 1),
+    (700, 37, 5, 16, 2, 128, 0),      # prefix rows, ragged everything
+    (700, 37, 5, 16, 2, 128, 1),
+    (1000, 130, 0, 10, 2, 128, 0),    # group 5
+    (333, 3, 0, 8, 8, 64, 0),         # group 1, fewer rows than one tile
+])
+def test_score_matches_oracle(B, V, L, P, hq, hkv, d, mode):
+    n_keys = P + V + L
+    q, k = rnd_bits((L, hq, d), 50 + V), rnd_bits((n_keys, hkv, d), 51 + V)
+    scale = 1 / np.sqrt(d)
+    want, want_lse = oracle.score(q, k, P, V, P + V, scale, norm_mode=mode, want_lse=True)
+    qd, kd = dev_bf16(q), dev_bf16(k)
+    got = B.score(qd, kd, P, V, P + V, scale, norm_mode=mode)
+    torch.cuda.synchronize()
+    assert_scores_close(got, want, f"V{V} L{L} mode{mode}")
+    # caller-supplied row normalisers skip the first sweep and give the same scores
+    lse = torch.tensor(want_lse, dtype=torch.float32).cuda()
+    got2 = B.score(qd, kd, P, V, P + V, scale, norm_mode=mode, row_lse=lse)
+    torch.cuda.synchronize()
+    assert_scores_close(got2, want, f"V{V} L{L} mode{mode} row_lse")
+
+
+def test_score_text_queries_inside_video_span_are_causal(B):
+    V, L, hq, hkv, d = 300, 40, 4, 2, 64
+    q, k = rnd_bits((L, hq, d), 60), rnd_bits((V + L, hkv, d), 61)
+    pos0 = V - 25                      # the first queries cannot see the last video keys
+    for mode in (0, 1):
+        want = oracle.score(q, k, 0, V, pos0, 0.125, norm_mode=mode)
+        got = B.score(dev_bf16(q), dev_bf16(k), 0, V, pos0, 0.125, norm_mode=mode)
+        torch.cuda.synchronize()
+        assert_scores_close(got, want, f"causal mode{mode}")
+
+
+def test_score_beta_accumulates_layers(B):
+    w = synth.TINY
+    t0, t1 = synth.make_layer(w, 0), synth.make_layer(w, 1)
+    a0 = oracle.score(t0["q_text"], t0["k"][:w.n_ctx], 0, w.n_video, w.n_video, w.softmax_scale)
+    a1 = oracle.score(t1["q_text"], t1["k"][:w.n_ctx], 0, w.n_video, w.n_video, w.softmax_scale,
+                      beta=1.0, scores_in=a0)
+    s = B.score(dev_bf16(t0["q_text"]), dev_bf16(t0["k"][:w.n_ctx]), 0, w.n_video, w.n_video, w.softmax_scale)
+    s = B.score(dev_bf16(t1["q_text"]), dev_bf16(t1["k"][:w.n_ctx]), 0, w.n_video, w.n_video,
+                w.softmax_scale, beta=1.0, scores=s)
+    torch.cuda.synchronize()
+    assert_scores_close(s, a1, "beta")
+
+
+def test_score_planted_keys_on_top_and_chain_to_select(B):
+    """score -> select end to end on the Tiny workload: every planted key lands
+    in V_R, and the kept set differs from the oracle chain only among tokens
+    whose oracle score is within 1e-3 (relative) of the k-th score."""
+    w = synth.TINY
+    t = synth.make_layer(w)
+    want = oracle.score(t["q_text"], t["k"][:w.n_ctx], 0, w.n_video, w.n_video, w.softmax_scale)
+    got = B.score(dev_bf16(t["q_text"]), dev_bf16(t["k"][:w.n_ctx]), 0, w.n_video, w.n_video, w.softmax_scale)
+    keep, flag = B.select(got, i32(w.k_top), i32(w.keep_budget), w.keep_budget)
+    torch.cuda.synchronize()
+    keep, flag = keep.cpu().numpy(), flag.cpu().numpy()
+    top = set(keep[flag == 1].tolist())
+    assert set(t["planted"].tolist()) <= top
+    okeep, oflag = oracle.select(want.astype(np.float32), w.k_top, w.keep_budget)
+    otop = set(okeep[oflag == 1].tolist())
+    kth = np.sort(want)[::-1][w.k_top - 1]
+    for j in top ^ otop:
+        assert abs(want[j] - kth) <= 1e-3 * kth
+
+
+def test_score_argument_errors(B):
+    q = torch.zeros((4, 4, 64), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((20, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.SpecVLMError) as e:
+        B.score(q, k, 10, 16, 16, 0.1)             # video span beyond the keys
+    assert e.value.status == -1
+    with pytest.raises(B.SpecVLMError):
+        B.score(q, k, 0, 16, 16, 0.1, norm_mode=3)
+
+
+# ----------------------------------------------------------------- select
+@pytest.mark.parametrize("V,k,Bud,seed,levels", [
+    (1568, 78, 157, 0, 0), (6272, 313, 627, 1, 0), (12544, 627, 1254, 2, 0),
+    (32768, 1638, 3277, 3, 0), (32768, 8192, 16384, 4, 0), (32768, 4096, 8192, 5, 8),
+    (200, 0, 20, 6, 0), (200, 20, 20, 7, 0), (97, 13, 41, 8, 2), (64, 5, 64, 9, 0),
+    (1, 1, 1, 10, 0), (5000, 0, 0, 11, 0), (40000, 2000, 4000, 12, 0), (65536, 100, 6000, 13, 3),
+    (1025, 1, 1025, 14, 0), (3000, 300, 600, 15, 1),
+])
+def test_select_bit_exact(B, V, k, Bud, seed, levels):
+    s = synth.make_scores(V, seed, levels=levels)
+    want_keep, want_flag = oracle.select(s, k, Bud)
+    keep, flag = B.select(torch.from_numpy(s).cuda(), i32(k), i32(Bud), Bud)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(keep.cpu().numpy(), want_keep)
+    np.testing.assert_array_equal(flag.cpu().numpy(), want_flag)
+
+
+def test_select_special_values(B):
+    s = np.array([0.0, -0.0, 0.0, np.nan, -1.0, -0.0, np.inf, -np.inf, 1e-40, -1e-40], np.float32)
+    for k, Bud in ((3, 3), (5, 5), (1, 4), (6, 9), (10, 10)):
+        want_keep, want_flag = oracle.select(s, k, Bud)
+        keep, flag = B.select(torch.from_numpy(s).cuda(), i32(k), i32(Bud), Bud)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(keep.cpu().numpy(), want_keep)
+        np.testing.assert_array_equal(flag.cpu().numpy(), want_flag)
+
+
+def test_select_ragged_batch_in_one_launch(B):
+    frames = synth.ragged_frames()
+    Vs = (frames * 196).astype(np.int64)
+    buds = (Vs * 10 + 50) // 100
+    ks = buds // 2
+    scores = [synth.make_scores(int(v), 70 + i, levels=(4 if i == 3 else 0)) for i, v in enumerate(Vs)]
+    cu_v = i32(np.concatenate([[0], np.cumsum(Vs)]))
+    cu_k = i32(np.concatenate([[0], np.cumsum(buds)]))
+    keep, flag, status = B.select(torch.from_numpy(np.concatenate(scores)).cuda(), i32(ks), i32(buds),
+                                  int(buds.sum()), cu_video=cu_v, cu_keep=cu_k,
+                                  max_n_video=int(Vs.max()), want_status=True)
+    torch.cuda.synchronize()
+    assert status.cpu().numpy().tolist() == [0] * len(Vs)
+    keep, flag = keep.cpu().numpy(), flag.cpu().numpy()
+    o = 0
+    for i in range(len(Vs)):
+        wk, wf = oracle.select(scores[i], int(ks[i]), int(buds[i]))
+        np.testing.assert_array_equal(keep[o:o + buds[i]], wk)
+        np.testing.assert_array_equal(flag[o:o + buds[i]], wf)
+        o += int(buds[i])
+
+
+def test_select_device_side_budget_errors(B):
+    s = torch.from_numpy(synth.make_scores(100, 80)).cuda()
+    keep = B.select(s, i32(5), i32(3), 3, want_status=True)          # k_top > keep_budget
+    torch.cuda.synchronize()
+    assert keep[2].item() == -1
+    with pytest.raises(B.SpecVLMError):
+        B.select(s, i32(1), i32(2), 200)                              # total_keep > tokens
+
+
+# ----------------------------------------------------------------- gather
+@pytest.mark.parametrize("layers,P,V,L,hkv,d,keep_n", [
+    (1, 0, 1568, 64, 1, 64, 157), (3, 4, 500, 33, 2, 128, 77), (2, 0, 300, 0, 8, 128, 300),
+    (2, 0, 300, 10, 4, 64, 0), (24, 0, 1254, 262, 2, 64, 125),
+])
+def test_gather_bit_exact(B, layers, P, V, L, hkv, d, keep_n):
+    n_keys = P + V + L
+    k, v = rnd_bits((layers, n_keys, hkv, d), 90 + V), rnd_bits((layers, n_keys, hkv, d), 91 + V)
+    keep = np.sort(np.random.default_rng(92).choice(V, keep_n, replace=False)).astype(np.int32)
+    kd, vd = B.gather_kv(dev_bf16(k), dev_bf16(v), P, V, i32(keep) if keep_n else torch.zeros(0, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    for l in range(layers):
+        np.testing.assert_array_equal(host_bits(kd[l]), oracle.gather_kv(k[l], P, V, keep))
+        np.testing.assert_array_equal(host_bits(vd[l]), oracle.gather_kv(v[l], P, V, keep))
+
+
+def test_gather_head_major_source_and_destination(B):
+    layers, V, L, hkv, d = 2, 400, 16, 4, 128
+    k = rnd_bits((layers, V + L, hkv, d), 95)
+    keep = np.arange(0, V, 7, dtype=np.int32)
+    src = dev_bf16(k).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)       # stored [l, h, t, d]
+    n_dst = L + keep.size
+    dst = torch.zeros((layers, hkv, n_dst, d), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    B.gather_kv(src, None, 0, V, i32(keep), k_dst=dst)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        np.testing.assert_array_equal(host_bits(dst[l]), oracle.gather_kv(k[l], 0, V, keep))
+
+
+def test_attention_over_gathered_cache(B):
+    """The draft's decode over the gathered cache equals the oracle's attention
+    over the oracle's gather (the path select -> gather -> draft attention)."""
+    w = synth.TINY
+    t = synth.make_layer(w)
+    s = synth.make_scores(w.n_video, 5)
+    keep, _ = B.select(torch.from_numpy(s).cuda(), i32(w.k_top), i32(w.keep_budget), w.keep_budget)
+    kd, vd = B.gather_kv(dev_bf16(t["k"][None]), dev_bf16(t["v"][None]), 0, w.n_video, keep)
+    q = dev_bf16(t["q_block"][-1:])
+    out = B.decode_attn(q, kd[0], vd[0], w.softmax_scale)
+    torch.cuda.synchronize()
+    okeep, _ = oracle.select(s, w.k_top, w.keep_budget)
+    want, _ = oracle.decode_attn(t["q_block"][-1:], oracle.gather_kv(t["k"], 0, w.n_video, okeep),
+                                 oracle.gather_kv(t["v"], 0, w.n_video, okeep), w.softmax_scale)
+    from gpu_util import assert_attn_close
+    assert_attn_close(out, want, "draft over pruned cache")
