@@ -188,12 +188,12 @@ int specvlm_decode_attn(
 /* --------------------------------------------------------------------------
  * specvlm_accept -- which drafted tokens survive verification  (Sec. 2.1).
  *
- * Greedy (draft_logits == NULL and uniforms == NULL; App. A: the target decodes
+ * Greedy (uniforms == NULL, then draft_logits must be NULL too; App. A: the target decodes
  * greedily, output identical to the target's own): t_i = argmax of target row
  * i, lowest index on ties; n = length of the longest prefix with
  * draft_tokens[i] == t_i; out = x_0..x_{n-1}, t_n, then -1 padding.
  *
- * Rejection sampling (both given; the speculative-sampling rule the paper
+ * Rejection sampling (uniforms given, draft_logits required when gamma > 0; the speculative-sampling rule the paper
  * builds on, which preserves the target's output distribution): with p_i, q_i
  * the softmax of target / draft row i at `temperature`, accept x_i iff
  * u_i * q_i[x_i] < p_i[x_i], stop at the first rejection (n accepted); the

@@ -33,7 +33,8 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_decode_attn", "oracle_score", "oracle_select", "oracle_top_p_count",
-                     "oracle_gather_kv", "oracle_accept_greedy", "oracle_accept_sample"):
+                     "oracle_gather_kv", "oracle_accept_greedy", "oracle_accept_sample",
+                     "oracle_final_token_interval"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -142,3 +143,17 @@ def accept_sample(target_logits, draft_logits, draft_tokens, uniforms, temperatu
     if rc:
         raise ValueError(f"oracle_accept_sample rc={rc}")
     return int(n.value), out, margins
+
+
+def final_token_interval(target_logits, draft_logits, n: int, token: int, temperature: float = 1.0
+                         ) -> Tuple[float, float]:
+    """Normalised CDF interval [lo, hi) of `token` in the final draw after n accepted drafts."""
+    t = np.ascontiguousarray(target_logits, dtype=np.float32)
+    gamma, vocab = t.shape[0] - 1, t.shape[1]
+    dl = np.ascontiguousarray(draft_logits, dtype=np.float32).reshape(gamma, vocab)
+    lo, hi = C.c_double(0), C.c_double(0)
+    rc = lib().oracle_final_token_interval(_p(t), _p(dl), n, gamma, vocab, C.c_double(temperature),
+                                           token, C.byref(lo), C.byref(hi))
+    if rc:
+        raise ValueError(f"oracle_final_token_interval rc={rc}")
+    return lo.value, hi.value

@@ -375,3 +375,30 @@ int oracle_accept_sample(const float* target_logits /* [gamma+1, vocab] */,
     free(p); free(q); free(w);
     return 0;
 }
+
+/* The final draw's distribution after n accepted drafts, as a normalised CDF
+ * interval [lo, hi) of one token: lets a test check that a token returned for
+ * the uniform u_gamma satisfies lo <= u_gamma < hi up to a stated slack, where
+ * rounding decides between neighbouring tokens. */
+int oracle_final_token_interval(const float* target_logits, const float* draft_logits,
+                                int n, int gamma, int vocab, double temperature, int token,
+                                double* lo, double* hi)
+{
+    if (n < 0 || n > gamma || vocab < 1 || token < 0 || token >= vocab || !(temperature > 0.0)) return -1;
+    double* p = (double*)malloc(sizeof(double) * (size_t)vocab);
+    double* q = (double*)malloc(sizeof(double) * (size_t)vocab);
+    if (!p || !q) { free(p); free(q); return -2; }
+    softmax_f64(target_logits + (long)n * vocab, vocab, 1.0 / temperature, p);
+    if (n < gamma) {
+        softmax_f64(draft_logits + (long)n * vocab, vocab, 1.0 / temperature, q);
+        for (int v = 0; v < vocab; ++v) p[v] = p[v] - q[v] > 0.0 ? p[v] - q[v] : 0.0;
+    }
+    double W = 0.0, below = 0.0;
+    for (int v = 0; v < vocab; ++v) W += p[v];
+    for (int v = 0; v < token; ++v) below += p[v];
+    if (!(W > 0.0)) { free(p); free(q); return -3; }
+    *lo = below / W;
+    *hi = (below + p[token]) / W;
+    free(p); free(q);
+    return 0;
+}

@@ -145,7 +145,8 @@ def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video
 # -------------------------------------------------------------------------- select
 def select(scores: torch.Tensor, k_top: torch.Tensor, keep_budget: torch.Tensor, total_keep: int,
            *, cu_video: Optional[torch.Tensor] = None, cu_keep: Optional[torch.Tensor] = None,
-           max_n_video: Optional[int] = None, want_flags: bool = True, want_status: bool = False):
+           max_n_video: Optional[int] = None, want_flags: bool = True, want_status: bool = False,
+           keep_idx: Optional[torch.Tensor] = None):
     """scores fp32 [sum V_b]; k_top/keep_budget device int32 [batch] -> keep_idx int32 [total_keep]."""
     batch = k_top.numel()
     if max_n_video is None:
@@ -153,7 +154,8 @@ def select(scores: torch.Tensor, k_top: torch.Tensor, keep_budget: torch.Tensor,
             raise ValueError("max_n_video is required with cu_video")
         max_n_video = scores.numel()
     dev = scores.device
-    keep_idx = torch.empty(total_keep, dtype=torch.int32, device=dev)
+    if keep_idx is None:
+        keep_idx = torch.empty(total_keep, dtype=torch.int32, device=dev)
     flags = torch.empty(total_keep, dtype=torch.uint8, device=dev) if want_flags else None
     status = torch.empty(batch, dtype=torch.int32, device=dev) if want_status else None
     rc = lib().specvlm_select(_ptr(scores), _ptr(cu_video), _ptr(k_top), _ptr(keep_budget),
@@ -237,13 +239,15 @@ def accept_workspace_bytes(batch, gamma, vocab, sampling) -> int:
 
 def accept(target_logits: torch.Tensor, draft_tokens: torch.Tensor, *,
            draft_logits: Optional[torch.Tensor] = None, uniforms: Optional[torch.Tensor] = None,
-           temperature: float = 1.0, workspace: Optional[torch.Tensor] = None):
+           temperature: float = 1.0, workspace: Optional[torch.Tensor] = None,
+           n_accepted: Optional[torch.Tensor] = None, out_tokens: Optional[torch.Tensor] = None):
     """target_logits fp32 [batch, gamma+1, vocab] -> (n_accepted int32 [batch], out_tokens int32 [batch, gamma+1])."""
     batch, g1, vocab = target_logits.shape
     gamma = g1 - 1
     dev = target_logits.device
-    n_acc = torch.empty(batch, dtype=torch.int32, device=dev)
-    out = torch.empty((batch, gamma + 1), dtype=torch.int32, device=dev)
+    n_acc = n_accepted if n_accepted is not None else torch.empty(batch, dtype=torch.int32, device=dev)
+    out = out_tokens if out_tokens is not None else \
+        torch.empty((batch, gamma + 1), dtype=torch.int32, device=dev)
     sampling = uniforms is not None
     need = accept_workspace_bytes(batch, gamma, vocab, sampling)
     workspace = _ws(workspace, need, target_logits)

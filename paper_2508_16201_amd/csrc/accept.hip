@@ -149,6 +149,7 @@ void accept_sample_final(const AcceptParams p)
         int n = 0;
         for (; n < p.gamma; ++n) {
             const int tok = x[n];
+            if (tok < 0 || tok >= p.vocab) break;           // not a token: cannot be accepted
             const float pt = fast_exp2(tgt[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[n]) / s_z[n];
             const float qd = fast_exp2(drf[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[p.gamma + 1 + n]) /
                              s_z[p.gamma + 1 + n];
@@ -259,8 +260,9 @@ extern "C" int specvlm_accept(
     void* workspace, size_t workspace_bytes, void* stream)
 {
     if (batch < 0 || gamma < 0 || vocab < 1) return SPECVLM_EINVAL;
-    if ((draft_logits == nullptr) != (uniforms == nullptr)) return SPECVLM_EINVAL;
     const bool sampling = uniforms != nullptr;
+    if (!sampling && draft_logits) return SPECVLM_EINVAL;            // draft logits without uniforms
+    if (sampling && gamma > 0 && !draft_logits) return SPECVLM_EINVAL;
     if (sampling && !(temperature > 0.f && temperature < INFINITY)) return SPECVLM_EINVAL;
     if (gamma > 64) return SPECVLM_EUNSUPPORTED;
     if (batch == 0) return SPECVLM_OK;

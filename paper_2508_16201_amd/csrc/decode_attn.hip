@@ -328,36 +328,61 @@ void attn_split_kernel(const AttnParams p)
 }
 
 // Merge of the split partials: o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s.
-// One thread owns 4 output columns of one query row.
+// One workgroup per (kv head, query row).  All loads of a phase are independent
+// (one split per thread for the statistics, splits strided over thread groups
+// for the outputs), so the kernel costs a few memory round trips, not one per split.
 template <int D>
 __global__ __launch_bounds__(256)
 void attn_merge_kernel(const AttnParams p)
 {
-    constexpr int TPR = D / 4;                       // threads per row
-    constexpr int ROWS = 256 / TPR;
-    const int bh = blockIdx.y;
+    constexpr int TPR = D / 4;                       // threads that cover one row of D columns
+    constexpr int GROUPS = 256 / TPR;                // split groups working in parallel
+    __shared__ float s_w[kMaxSplits];
+    __shared__ float s_red[8];
+    __shared__ __align__(16) float s_acc[GROUPS][D];
+    const int row = blockIdx.x, bh = blockIdx.y;
     const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
     int q0 = 0, ql = p.q_len, kvl = p.kv_len;
     if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
     if (p.cu_kv) { kvl = p.cu_kv[b + 1] - p.cu_kv[b]; }
-    if (ql <= 0 || kvl < ql) return;
-    const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
-    if (row >= p.group * ql) return;
-    const int col = (threadIdx.x % TPR) * 4;
+    if (ql <= 0 || kvl < ql || row >= p.group * ql) return;
     const int live = min(p.num_splits, (kvl + p.split_keys - 1) / p.split_keys);
     const int64_t slot0 = (int64_t)bh * p.num_splits * p.rows_pad + row;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    float m = -INFINITY;
-    for (int s = 0; s < live; ++s) m = fmaxf(m, p.part_ml[(slot0 + (int64_t)s * p.rows_pad) * 2]);
-    const float m_ref = (m == -INFINITY) ? 0.f : m;
-    float l = 0.f;
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < live; ++s) {
-        const int64_t slot = slot0 + (int64_t)s * p.rows_pad;
-        const float w = fast_exp2(p.part_ml[slot * 2] - m_ref);
-        l += w * p.part_ml[slot * 2 + 1];
-        acc += w * *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+    // phase 1: one split per thread -> global max, weights, total sum
+    float m_s = -INFINITY, l_s = 0.f;
+    if (tid < live) {
+        const float* ml = p.part_ml + (slot0 + (int64_t)tid * p.rows_pad) * 2;
+        m_s = ml[0]; l_s = ml[1];
     }
+    float m = m_s;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    const float m_ref = (m == -INFINITY) ? 0.f : m;
+    const float w_s = (tid < live) ? fast_exp2(m_s - m_ref) : 0.f;
+    s_w[tid] = w_s;
+    float l = w_s * l_s;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
+    if (lane == 0) s_red[4 + wave] = l;
+    __syncthreads();
+    l = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+
+    // phase 2: group `grp` accumulates splits grp, grp+GROUPS, ... for 4 columns
+    const int grp = tid / TPR, col = (tid % TPR) * 4;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = grp; s < live; s += GROUPS)
+        acc += s_w[s] * *reinterpret_cast<const floatx4*>(
+                            p.part_o + (slot0 + (int64_t)s * p.rows_pad) * D + col);
+    *reinterpret_cast<floatx4*>(&s_acc[grp][col]) = acc;
+    __syncthreads();
+    if (grp != 0) return;
+#pragma unroll
+    for (int gg = 1; gg < GROUPS; ++gg) acc += *reinterpret_cast<const floatx4*>(&s_acc[gg][col]);
     acc *= 1.f / l;
     const int t = row / p.group, h = g * p.group + row % p.group;
     __bf16* op = p.out + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + col;
@@ -460,6 +485,9 @@ extern "C" int specvlm_decode_attn(
     const int group = n_q_heads / n_kv_heads;
     const int rows = group * q_len;
     if (rows > 64) return SPECVLM_EUNSUPPORTED;
+    // per-lane key offsets are 32-bit byte offsets from the request's first row
+    if (kv_tok_stride <= 0 || (int64_t)kv_len * kv_tok_stride * 2 >= ((int64_t)1 << 32))
+        return SPECVLM_EUNSUPPORTED;
     const int mb = (rows + 15) / 16;
 
     AttnParams p;
@@ -489,8 +517,7 @@ extern "C" int specvlm_decode_attn(
     int rc = head_dim == 128 ? launch_attn_d<128>(p, mb, s) : launch_attn_d<64>(p, mb, s);
     if (rc != SPECVLM_OK) return rc;
     if (p.num_splits > 1) {
-        const int rows_per_block = 256 / (head_dim / 4);
-        dim3 grid((rows + rows_per_block - 1) / rows_per_block, batch * n_kv_heads);
+        dim3 grid(rows, batch * n_kv_heads);
         if (head_dim == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL(attn_merge_kernel<64>, grid, dim3(256), 0, s, p);
         rc = launch_status();

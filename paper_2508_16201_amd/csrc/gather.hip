@@ -29,7 +29,8 @@ void gather_kernel(const GatherParams p)
     const int head = ch / p.chunks_per_head, e = (ch % p.chunks_per_head) * 8;
     int src_row;
     if (row < p.video_start) src_row = row;
-    else if (row < p.video_start + p.n_keep) src_row = p.video_start + p.keep_idx[row - p.video_start];
+    else if (row < p.video_start + p.n_keep)     // indices are clamped into the video span
+        src_row = p.video_start + min(max(p.keep_idx[row - p.video_start], 0), p.n_video - 1);
     else src_row = row - p.n_keep + p.n_video;
     const __bf16* s = p.src[which] + layer * p.src_layer + (int64_t)src_row * p.src_tok +
                       (int64_t)head * p.src_head + e;

@@ -67,10 +67,12 @@ def test_bad_arguments_are_rejected_before_any_launch(B):
     assert rc == -1
     rc = lib.specvlm_gather_kv(null, null, 0, 0, 0, null, null, 0, 0, 0, 1, 10, 0, 4, null, 5, 2, 128, null)
     assert rc == -1
-    # accept: gamma < 0, vocab < 1, uniforms without draft logits
+    # accept: gamma < 0, vocab < 1, draft logits without uniforms
     rc = lib.specvlm_accept(null, null, null, null, 1, -1, 10, 1.0, null, null, null, 0, null)
     assert rc == -1
     rc = lib.specvlm_accept(null, null, null, null, 1, 2, 0, 1.0, null, null, null, 0, null)
+    assert rc == -1
+    rc = lib.specvlm_accept(null, C.c_void_p(8), null, null, 1, 2, 10, 1.0, null, null, null, 0, null)
     assert rc == -1
     # select: negative sizes; batch > 1 without cu arrays
     rc = lib.specvlm_select(null, null, null, null, null, -1, 10, 1, null, null, null, null, 0, null)

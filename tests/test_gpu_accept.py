@@ -89,9 +89,15 @@ def test_sampling_matches_oracle_outside_margin(B, batch, gamma, vocab, temp):
         assert np.all(out[b][wn + 1:] == -1)
         if margins[gamma] >= MARGIN:
             assert out[b][wn] == wout[wn], (b, out[b][wn], wout[wn], margins[gamma])
-            checked += 1
         else:
-            skipped += 1
+            # the uniform sits within 1e-4 of a CDF step: any token whose own
+            # interval reaches within that slack of the uniform is correct
+            lo, hi = oracle.final_token_interval(inp["target_logits"][b], inp["draft_logits"][b],
+                                                 wn, int(out[b][wn]), temp)
+            u = float(inp["uniforms"][b][gamma])
+            assert hi > lo and lo - MARGIN <= u <= hi + MARGIN, (b, out[b][wn], wout[wn], lo, u, hi)
+        checked += 1
+    # the accept/reject tests themselves rarely sit inside the margin
     assert checked >= 0.9 * batch, (checked, skipped)
 
 

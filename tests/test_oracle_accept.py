@@ -97,6 +97,26 @@ def test_threshold_and_residual_by_hand():
         assert n == 1 and out[1] == tok
 
 
+def test_final_token_interval_brackets_the_draw():
+    p = np.array([.5, .3, .2]); q = np.array([.2, .6, .2])
+    t = np.log(np.stack([p, p])).astype(np.float32)
+    dl = np.log(q)[None].astype(np.float32)
+    # after 1 accepted (bonus draw from p): cdf .5/.8/1
+    for tok, (lo, hi) in enumerate(((0, .5), (.5, .8), (.8, 1.0))):
+        a, b = oracle.final_token_interval(t, dl, 1, tok)
+        assert abs(a - lo) < 1e-7 and abs(b - hi) < 1e-7
+    # after a rejection at 0: residual (.3,0,0)/.3 -> token 0 owns [0,1)
+    assert oracle.final_token_interval(t, dl, 0, 0) == pytest.approx((0.0, 1.0))
+    a, b = oracle.final_token_interval(t, dl, 0, 2)
+    assert a == pytest.approx(1.0) and b == pytest.approx(1.0)
+    # consistent with the sampler on random inputs
+    inp = synth.make_accept_inputs(1, 3, 200, 21, sigma=1.0, greedy=False)
+    n, out, _ = oracle.accept_sample(inp["target_logits"][0], inp["draft_logits"][0],
+                                     inp["draft_tokens"][0], inp["uniforms"][0])
+    lo, hi = oracle.final_token_interval(inp["target_logits"][0], inp["draft_logits"][0], n, int(out[n]))
+    assert lo <= inp["uniforms"][0][3] < hi
+
+
 def test_temperature_scales_logits():
     p = np.array([.5, .3, .2]); q = np.array([.2, .6, .2])
     T = 2.0
