@@ -258,14 +258,21 @@ def main():
     }
 
     if not args.no_cpu_baseline:
+        # The fp64 oracle as it stands, on the host cores, over the same layer-0
+        # inputs: repeated whole-layer passes for about 10 s (at most 30 s).
         import oracle
         cores = len(os.sched_getaffinity(0))
-        t0 = time.perf_counter()
-        oracle.decode_attn(host0["q_block"], host0["k"], host0["v"], scale, want_lse=False)
-        dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(attn_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": cores,
-                                  "kind": "oracle",
-                                  "sample": f"verify attention of 1 of {L} layers (fp64 oracle, {dt:.2f} s)"}
+        passes, t0 = 0, time.perf_counter()
+        while True:
+            oracle.decode_attn(host0["q_block"], host0["k"], host0["v"], scale, want_lse=False)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or (passes >= 1 and dt * (passes + 1) / passes > 30.0):
+                break
+        result["cpu_baseline"] = {"value": round(attn_bytes * passes / dt / 1e9, 4), "unit": "GB/s",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"{passes} passes of the verify attention of layer 0 of {L} "
+                                            f"(fp64 oracle, {dt:.1f} s, OpenMP over query rows)"}
     print(json.dumps(result))
 
 

@@ -3,30 +3,40 @@
 // paper) over a long bf16 KV cache, in split-K (flash-decode) form for gfx950.
 //
 // Work decomposition
-//   One workgroup (4 waves) owns one (request, kv head, key split).  All
-//   G*q_len query rows that share the kv head are packed into the MFMA "row"
-//   dimension (up to 4 blocks of 16 rows), so every K/V byte is read from HBM
-//   exactly once.  Inside the workgroup the split's 32-key tiles are dealt
-//   round-robin to the 4 waves; each wave runs an independent online softmax
-//   and the four partial results are merged through LDS at the end.
+//   One workgroup owns one (request, kv head, key split).  All G*q_len query
+//   rows that share the kv head are packed into MFMA row blocks of 16 (MB of
+//   them, MB <= 4), so every K/V byte is read from HBM exactly once.  The
+//   workgroup has MB*KS waves: wave (mb, ks) owns row block mb and every KS-th
+//   32-key chunk of each tile, so a wave carries one 16-row accumulator only.
+//
+// Data movement
+//   K/V tiles of TK keys stream HBM -> LDS with direct-to-LDS loads
+//   (global_load_lds_dwordx4: no registers in between) into a ring of NS
+//   stages; NS-1 tiles are in flight while one is consumed.  A stage is
+//   released by one s_barrier per tile; the waves wait on their own vmcnt for
+//   the tile they are about to read, never on the younger tiles.  K rows are
+//   stored with their 16-byte chunks XOR-swizzled by the key index so that the
+//   MFMA operand reads (16 keys x one chunk per 16 lanes) hit distinct banks;
+//   the swizzle is applied on the global-address side, the LDS side of a
+//   direct load being fixed (lane * 16 bytes).
 //
 // MFMA formulation (v_mfma_f32_16x16x32_bf16, lane = 16*c + r)
-//   S^T = K Q^T : A = K tile (rows = 16 keys, contraction = d), B = Q^T.  The
-//     result puts query row r in lane column r and keys 4c..4c+3 in the four
-//     accumulator registers, so all softmax statistics of a row live in the
-//     lanes r, r+16, r+32, r+48.
-//   O^T = V^T P^T : B = P^T is exactly what the lane already holds (row r, the
-//     8 keys {4c..4c+3} of both 16-key sub-tiles); A = V^T needs, per lane, 8
-//     keys x 1 value column.  Each lane loads 8 (d=128) contiguous value
-//     columns of its 8 keys (a full 256-byte row per 16 lanes) and an in-lane
-//     16-bit transpose (v_perm) forms the operands.  The contraction order over
-//     keys and the column order of O are permutations fixed by this layout, so
-//     neither K nor V ever goes through LDS.
-//   O^T keeps row r in lane column r as well: rescaling by the running max is a
-//     per-lane multiply.
+//   S^T = K Q^T : A = K chunk (rows = 16 keys, contraction = d), B = Q^T.  Query
+//     row r sits in lane column r, keys 4c..4c+3 in the four accumulators: the
+//     softmax statistics of a row live in lanes r, r+16, r+32, r+48.
+//   O^T = V^T P^T : B = P^T is what the lane already holds (row r, keys
+//     {4c..4c+3} of both 16-key halves); A = V^T needs per lane 8 keys x 1 value
+//     column.  A lane reads 8 (d=128) contiguous value columns of its 8 keys
+//     and an in-lane 16-bit transpose (v_perm) forms the operands.  The
+//     contraction order over keys and the column order of O are permutations
+//     fixed by this layout.  O^T keeps row r in lane column r too, so the
+//     running-max rescale is a per-lane multiply.
 #include "common.h"
 
 namespace specvlm {
+
+#define SPECVLM_AS1 __attribute__((address_space(1)))
+#define SPECVLM_AS3 __attribute__((address_space(3)))
 
 struct AttnParams {
     const __bf16* q;
@@ -46,21 +56,81 @@ struct AttnParams {
     int n_work, n_work_padded;
 };
 
-constexpr int kTileKeys = 32;
-constexpr int kAttnWaves = 4;
+constexpr int kChunkKeys = 32;       // keys per PV contraction step
 constexpr int kMaxSplits = 256;
+
+// s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
+constexpr int vmcnt_imm(int n)
+{
+    return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8);
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(N));
+}
+
+// Workgroup barrier that does not drain the direct-to-LDS loads still in
+// flight for younger stages (a fence would).  Ordering of this wave's own LDS
+// traffic is handled by the s_waitcnt the compiler places before each use.
+__device__ __forceinline__ void stage_barrier()
+{
+    __asm__ volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __asm__ volatile("" ::: "memory");
+}
+
+// Reductions over the four lanes r, r+16, r+32, r+48 that share a query row,
+// with the VALU lane-swap instructions of gfx950 (no LDS crossbar round trip):
+// v_permlane32_swap exchanges the upper 32 lanes of one operand with the lower
+// 32 of the other, v_permlane16_swap the odd 16-lane rows with the even ones.
+__device__ __forceinline__ float quad_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+__device__ __forceinline__ float quad_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+constexpr int largest_divisor_le(int n, int cap)
+{
+    int best = 1;
+    for (int d = 1; d <= cap; ++d) if (n % d == 0) best = d;
+    return best;
+}
 
 template <int D> struct ValueVec;
 template <> struct ValueVec<128> { typedef u32x4 type; };
 template <> struct ValueVec<64>  { typedef u32x2 type; };
 
-template <int D, int MB>
-__global__ __launch_bounds__(kAttnWaves * kWave)
+template <int D, int MB, int KS, int TK, int NS>
+__global__ __launch_bounds__(MB * KS * kWave)
 void attn_split_kernel(const AttnParams p)
 {
-    constexpr int DJ = D / 16;          // value columns per lane (8 or 4)
-    constexpr int KK = D / 32;          // MFMA steps over the head dimension
-    constexpr int LDS_STRIDE = D + 4;
+    constexpr int NW = MB * KS;                  // waves per workgroup
+    constexpr int DJ = D / 16;                   // value columns per lane (8 or 4)
+    constexpr int KK = D / 32;                   // MFMA steps over the head dimension
+    constexpr int CH = D / 8;                    // 16-byte chunks per key row
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int KEYS_PER_LOAD = kWave / CH;    // key rows one wave-wide load covers (4 or 8)
+    constexpr int TILE_BYTES = TK * ROW_BYTES;   // one of K or V
+    constexpr int LOADS_PER_MAT = TK / KEYS_PER_LOAD;
+    constexpr int LOADS = 2 * LOADS_PER_MAT;     // wave-wide loads per stage (K then V)
+    constexpr int LW = largest_divisor_le(LOADS, NW);   // waves that issue loads
+    constexpr int LPW = LOADS / LW;              // loads per loader wave per stage
+    constexpr int NCHUNK = TK / kChunkKeys;      // 32-key chunks per tile
+    constexpr int LDS_STRIDE = D + 4;            // merge buffer row stride (floats)
+    static_assert(NCHUNK % KS == 0, "chunks must divide among the key-split waves");
+    static_assert(NS >= 2 && NS <= 6, "ring depth");
     typedef typename ValueVec<D>::type vvec_t;
 
     const int vid = xcd_logical_id(blockIdx.x, p.n_work_padded);
@@ -79,81 +149,91 @@ void attn_split_kernel(const AttnParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int mb = wave % MB, ks = wave / MB;
     const int r = lane & 15, c = lane >> 4;
     const int n_rows = p.group * ql;                // live query rows of this kv head
 
-    // ---- Q fragments (B operand of S^T) staged in LDS in fragment order: the
-    // waves re-read them per tile instead of pinning MB*KK*4 registers each ----
-    extern __shared__ __align__(16) float smem[];
-    u32x4* q_lds = reinterpret_cast<u32x4*>(smem);        // [MB][KK][64 lanes]
-    int last_key[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    // stage s: K tile at s*2*TILE_BYTES, V tile right after it
+
+    // ---- this wave's Q fragments (B operand of S^T) and the row's last visible key ----
+    bf16x8 qf[KK];
+    int last_key;
+    {
         const int row = mb * 16 + r;
         const bool live = row < n_rows;
         const int t = live ? row / p.group : 0;
         const int h = g * p.group + (live ? row % p.group : 0);
-        last_key[mb] = kvl - ql + t;
+        last_key = kvl - ql + t;
         const __bf16* qp = p.q + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + c * 8;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            if (((mb * KK + kk) & (kAttnWaves - 1)) != wave) continue;
             u32x4 raw = {0u, 0u, 0u, 0u};
             if (live) raw = *reinterpret_cast<const u32x4*>(qp + kk * 32);
-            q_lds[(mb * KK + kk) * kWave + lane] = raw;
+            qf[kk] = __builtin_bit_cast(bf16x8, raw);
         }
     }
-    __syncthreads();
 
-    // Uniform (scalar) request/head base plus 32-bit per-lane byte offsets.
     const char* kbase = reinterpret_cast<const char*>(p.k + (int64_t)kv0 * p.kv_tok + (int64_t)g * p.kv_head);
     const char* vbase = reinterpret_cast<const char*>(p.v + (int64_t)kv0 * p.kv_tok + (int64_t)g * p.kv_head);
     const uint32_t tok_bytes = (uint32_t)p.kv_tok * 2u;
-    const uint32_t k_lane = (uint32_t)c * 16u, v_lane = (uint32_t)r * (DJ * 2u);
 
-    float m_run[MB], l_run[MB];
-    floatx4 o_acc[MB][DJ];
+    // ---- loader: wave-wide direct-to-LDS loads; load n of a stage covers
+    // KEYS_PER_LOAD consecutive key rows of K (n < LOADS_PER_MAT) or of V ----
+    const int ld_key = lane / CH;                   // key row inside the load
+    const int ld_chunk = lane % CH;                 // LDS chunk slot inside the row
+    auto issue_tile = [&](int tile, int stage) {
+        const int base = k_begin + tile * TK;
+        unsigned char* st = smem + stage * (2 * TILE_BYTES);
+        if (wave >= LW) return;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        m_run[mb] = -INFINITY;
-        l_run[mb] = 0.f;
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) o_acc[mb][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    // Keys of a tile as seen by this lane: sub-tile 0 rows r (K operand) and, for
-    // the values / probabilities, keys 4c+i (i<4) and 16+4c+(i-4) (i>=4).
-    auto load_tile = [&](int base, u32x4 (&kr)[2][KK], vvec_t (&vr)[8]) {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            const uint32_t key = (uint32_t)min(base + kt * 16 + r, kvl - 1);
-            const char* kp = kbase + (key * tok_bytes + k_lane);
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                kr[kt][kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + kk * 64));
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t key = (uint32_t)min(base + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4)), kvl - 1);
-            vr[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const vvec_t*>(vbase + (key * tok_bytes + v_lane)));
+        for (int j = 0; j < LPW; ++j) {
+            const int n = wave + LW * j;
+            const bool is_v = n >= LOADS_PER_MAT;
+            const int kl = (is_v ? n - LOADS_PER_MAT : n) * KEYS_PER_LOAD + ld_key;   // key inside the tile
+            const uint32_t key = (uint32_t)min(base + kl, kvl - 1);
+            // K rows are chunk-swizzled so operand reads spread over the banks
+            const int swz = (D == 128) ? (kl & 15) : ((kl >> 1) & 7);
+            const int chunk = is_v ? ld_chunk : (ld_chunk ^ swz);
+            const char* src = (is_v ? vbase : kbase) + (key * tok_bytes + (uint32_t)chunk * 16u);
+            unsigned char* dst = st + n * 1024;     // + lane * 16 by the hardware
+            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src, (SPECVLM_AS3 void*)dst, 16, 0, 0);
         }
     };
 
-    auto compute_tile = [&](int base, const u32x4 (&kr)[2][KK], const vvec_t (&vr)[8]) {
-        const bool need_mask = (base + kTileKeys > k_end) || (base + kTileKeys - 1 > kvl - ql);
-        __asm__ volatile("" ::: "memory");       // keep the Q fragment reads inside the loop
-        bf16x8 pf[MB];
-        bool rescale = false;
-        float alpha[MB];
+    float m_run = -INFINITY, l_run = 0.f;
+    floatx4 o_acc[DJ];
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
+    for (int j = 0; j < DJ; ++j) o_acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute_tile = [&](int tile, int stage) {
+        const unsigned char* kt_lds = smem + stage * (2 * TILE_BYTES);
+        const unsigned char* vt_lds = kt_lds + TILE_BYTES;
+#pragma unroll
+        for (int cc = 0; cc < NCHUNK / KS; ++cc) {
+            const int chunk = ks + cc * KS;
+            const int base = k_begin + tile * TK + chunk * kChunkKeys;
+            if (base >= k_end) break;
+            const bool need_mask = (base + kChunkKeys > k_end) || (base + kChunkKeys - 1 > kvl - ql);
+            // ---- S^T = K Q^T for 32 keys ----
             floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 qf = __builtin_bit_cast(bf16x8, q_lds[(mb * KK + kk) * kWave + lane]);
-                s0 = mfma16(__builtin_bit_cast(bf16x8, kr[0][kk]), qf, s0);
-                s1 = mfma16(__builtin_bit_cast(bf16x8, kr[1][kk]), qf, s1);
+                const int x = kk * 4 + c;
+                const int key0 = chunk * kChunkKeys + r, key1 = key0 + 16;
+                const int sw0 = (D == 128) ? (key0 & 15) : ((key0 >> 1) & 7);
+                const int sw1 = (D == 128) ? (key1 & 15) : ((key1 >> 1) & 7);
+                const u32x4 k0 = *reinterpret_cast<const u32x4*>(kt_lds + key0 * ROW_BYTES + ((x ^ sw0) * 16));
+                const u32x4 k1 = *reinterpret_cast<const u32x4*>(kt_lds + key1 * ROW_BYTES + ((x ^ sw1) * 16));
+                s0 = mfma16(__builtin_bit_cast(bf16x8, k0), qf[kk], s0);
+                s1 = mfma16(__builtin_bit_cast(bf16x8, k1), qf[kk], s1);
+            }
+            // values of the lane's 8 keys: 4c+i (i<4) and 16+4c+(i-4)
+            vvec_t vr[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int kl = chunk * kChunkKeys + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
+                vr[i] = *reinterpret_cast<const vvec_t*>(vt_lds + kl * ROW_BYTES + r * (DJ * 2));
             }
             float s[8];
 #pragma unroll
@@ -162,167 +242,148 @@ void attn_split_kernel(const AttnParams p)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int key = base + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
-                    if (key >= k_end || key > last_key[mb]) s[i] = -INFINITY;
+                    if (key >= k_end || key > last_key) s[i] = -INFINITY;
                 }
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
                              fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[mb], mx);
+            mx = quad_max(mx);
+            const float m_new = fmaxf(m_run, mx);
             const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha[mb] = fast_exp2(m_run[mb] - m_ref);
-            rescale = rescale || (m_new != m_run[mb]);
-            m_run[mb] = m_new;
+            const float alpha = fast_exp2(m_run - m_ref);
+            const bool rescale = m_new != m_run;
+            m_run = m_new;
             floatx8 pv;
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(s[i] - m_ref); psum += pv[i]; }
-            l_run[mb] = l_run[mb] * alpha[mb] + psum;
-            pf[mb] = __builtin_convertvector(pv, bf16x8);
-        }
-        if (__any(rescale)) {
+            l_run = l_run * alpha + psum;
+            const bf16x8 pf = __builtin_convertvector(pv, bf16x8);
+            if (__any(rescale)) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+                for (int j = 0; j < DJ; ++j) o_acc[j] *= alpha;
+            }
+            // ---- O^T += V^T P^T ----
 #pragma unroll
-                for (int j = 0; j < DJ; ++j) o_acc[mb][j] *= alpha[mb];
-        }
+            for (int j = 0; j < DJ; ++j) {
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 vt;
 #pragma unroll
-        for (int j = 0; j < DJ; ++j) {
-            // in-lane transpose: value column j of the lane's 8 keys
-            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 vt;
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr)
-                vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][j >> 1], vr[2 * pr][j >> 1], sel);
-            const bf16x8 va = __builtin_bit_cast(bf16x8, vt);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) o_acc[mb][j] = mfma16(va, pf[mb], o_acc[mb][j]);
+                for (int pr = 0; pr < 4; ++pr)
+                    vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][j >> 1], vr[2 * pr][j >> 1], sel);
+                o_acc[j] = mfma16(__builtin_bit_cast(bf16x8, vt), pf, o_acc[j]);
+            }
         }
     };
 
-    // ---- stream the split's tiles, one tile of prefetch per wave ----
-    const int n_tiles = (k_end - k_begin + kTileKeys - 1) / kTileKeys;
-    {
-        u32x4 ka[2][KK], kb[2][KK];
-        vvec_t va[8], vb[8];
-        int ti = wave;
-        if (ti < n_tiles) load_tile(k_begin + ti * kTileKeys, ka, va);
-        while (ti < n_tiles) {
-            int tn = ti + kAttnWaves;
-            if (tn < n_tiles) load_tile(k_begin + tn * kTileKeys, kb, vb);
-            compute_tile(k_begin + ti * kTileKeys, ka, va);
-            ti = tn;
-            if (ti >= n_tiles) break;
-            tn = ti + kAttnWaves;
-            if (tn < n_tiles) load_tile(k_begin + tn * kTileKeys, ka, va);
-            compute_tile(k_begin + ti * kTileKeys, kb, vb);
-            ti = tn;
+    // ---- ring of NS stages: NS-1 tiles in flight while one is consumed ----
+    const int n_tiles = (k_end - k_begin + TK - 1) / TK;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < n_tiles) issue_tile(s, s);
+    for (int i = 0; i < n_tiles; ++i) {
+        // tiles issued after tile i so far: min(NS-2, n_tiles-1-i); each is LPW loads of this wave
+        const int younger = min(NS - 2, n_tiles - 1 - i);
+        switch (younger) {                           // (only values <= NS-2 occur)
+            case 0:  wait_vmcnt<0>(); break;
+            case 1:  wait_vmcnt<(NS >= 3 ? 1 : 0) * LPW>(); break;
+            case 2:  wait_vmcnt<(NS >= 4 ? 2 : 0) * LPW>(); break;
+            case 3:  wait_vmcnt<(NS >= 5 ? 3 : 0) * LPW>(); break;
+            default: wait_vmcnt<(NS >= 6 ? 4 : 0) * LPW>(); break;
         }
+        stage_barrier();                             // tile i landed for everyone; stage (i-1)%NS is free
+        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, (i + NS - 1) % NS);
+        compute_tile(i, i % NS);
     }
 
-    // ---- merge the four waves through LDS (reusing the Q staging area) ----
-    __syncthreads();
-    float* sm_m = smem;                              // [4][MB*16]
-    float* sm_l = sm_m + kAttnWaves * MB * 16;       // [4][MB*16]
-    float* sm_o = sm_l + kAttnWaves * MB * 16;       // [2][MB*16][LDS_STRIDE]
-    constexpr int OBUF = MB * 16 * LDS_STRIDE;
-
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        l_run[mb] += __shfl_xor(l_run[mb], 16);
-        l_run[mb] += __shfl_xor(l_run[mb], 32);
-        if (c == 0) sm_m[wave * MB * 16 + mb * 16 + r] = m_run[mb];
-    }
-    __syncthreads();
-    float m_all[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        float mm = sm_m[mb * 16 + r];
-#pragma unroll
-        for (int w = 1; w < kAttnWaves; ++w) mm = fmaxf(mm, sm_m[w * MB * 16 + mb * 16 + r]);
-        m_all[mb] = mm;
-        const float f = fast_exp2(m_run[mb] - ((mm == -INFINITY) ? 0.f : mm));
-        l_run[mb] *= f;
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) o_acc[mb][j] *= f;
-        if (c == 0) sm_l[wave * MB * 16 + mb * 16 + r] = l_run[mb];
-    }
-    // lane (r, c) holds columns [4*DJ*c, 4*DJ*(c+1)) of row r: column (4c+i)*DJ + j
-    auto lds_store = [&](float* buf) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+    // ---- epilogue ----
+    l_run = quad_sum(l_run);
+    const int row = mb * 16 + r;
+    const int t_row = row / p.group, h_row = g * p.group + row % p.group;
+    const int64_t slot = ((int64_t)bh * p.num_splits + split) * p.rows_pad + row;
+    if constexpr (KS == 1) {
+        // lane (r, c) holds columns (4c+i)*DJ + j of its row: write them out directly
+        if (p.num_splits == 1) {
+            if (row >= n_rows) return;
+            const float inv = 1.f / l_run;
+            __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[mb][4 * jj][i], o_acc[mb][4 * jj + 1][i],
-                                 o_acc[mb][4 * jj + 2][i], o_acc[mb][4 * jj + 3][i]};
-                    *reinterpret_cast<floatx4*>(buf + (mb * 16 + r) * LDS_STRIDE +
-                                                (4 * c + i) * DJ + 4 * jj) = x;
-                }
-    };
-    auto lds_add = [&](const float* buf) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DJ / 4; ++jj) {
-                    const floatx4 x = *reinterpret_cast<const floatx4*>(
-                        buf + (mb * 16 + r) * LDS_STRIDE + (4 * c + i) * DJ + 4 * jj);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o_acc[mb][4 * jj + e][i] += x[e];
-                }
-    };
-    if (wave & 1) lds_store(sm_o + (wave >> 1) * OBUF);
-    __syncthreads();
-    if (!(wave & 1)) lds_add(sm_o + (wave >> 1) * OBUF);
-    __syncthreads();
-    if (wave == 2) lds_store(sm_o);
-    __syncthreads();
-    if (wave != 0) return;
-    lds_add(sm_o);
-
-    const bool final_out = (p.num_splits == 1);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int row = mb * 16 + r;
-        float l_all = 0.f;
-#pragma unroll
-        for (int w = 0; w < kAttnWaves; ++w) l_all += sm_l[w * MB * 16 + row];
-        if (final_out) {
-            if (row >= n_rows) continue;
-            const int t = row / p.group, h = g * p.group + row % p.group;
-            const float inv = 1.f / l_all;
-            __bf16* op = p.out + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[mb][4 * jj][i], o_acc[mb][4 * jj + 1][i],
-                                 o_acc[mb][4 * jj + 2][i], o_acc[mb][4 * jj + 3][i]};
+                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
                     x *= inv;
-                    const bf16x4 y = __builtin_convertvector(x, bf16x4);
-                    *reinterpret_cast<bf16x4*>(op + (4 * c + i) * DJ + 4 * jj) = y;
+                    *reinterpret_cast<bf16x4*>(op + (4 * c + i) * DJ + 4 * jj) = __builtin_convertvector(x, bf16x4);
                 }
             if (p.lse && c == 0)
-                p.lse[(int64_t)(q0 + t) * p.n_q_heads + h] = (m_all[mb] + fast_log2(l_all)) * kLn2;
+                p.lse[(int64_t)(q0 + t_row) * p.n_q_heads + h_row] = (m_run + fast_log2(l_run)) * kLn2;
         } else {
-            const int64_t slot = ((int64_t)bh * p.num_splits + split) * p.rows_pad + row;
             float* po = p.part_o + slot * D;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[mb][4 * jj][i], o_acc[mb][4 * jj + 1][i],
-                                 o_acc[mb][4 * jj + 2][i], o_acc[mb][4 * jj + 3][i]};
+                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
                     *reinterpret_cast<floatx4*>(po + (4 * c + i) * DJ + 4 * jj) = x;
                 }
-            if (c == 0) {
-                p.part_ml[slot * 2] = m_all[mb];
-                p.part_ml[slot * 2 + 1] = l_all;
-            }
+            if (c == 0) { p.part_ml[slot * 2] = m_run; p.part_ml[slot * 2 + 1] = l_run; }
+        }
+    } else {
+        // The KS waves of a row block exchange their accumulators through LDS;
+        // afterwards wave ks owns the column slice [ks*D/KS, (ks+1)*D/KS) of all
+        // 16 rows, so every wave takes part in the final add and store.
+        constexpr int SLICE = D / KS;                // columns per wave after the exchange
+        constexpr int CPL = SLICE / 4;               // columns per lane (lane (r, c): c-th quarter)
+        __syncthreads();                             // every wave is done with the ring
+        float* sm_m = reinterpret_cast<float*>(smem);            // [NW][16]
+        float* sm_l = sm_m + NW * 16;                            // [NW][16]
+        float* sm_o = sm_l + NW * 16;                            // [NW][16][LDS_STRIDE]
+        if (c == 0) sm_m[wave * 16 + r] = m_run;
+        __syncthreads();
+        float m_all = m_run;
+#pragma unroll
+        for (int kx = 0; kx < KS; ++kx) m_all = fmaxf(m_all, sm_m[(kx * MB + mb) * 16 + r]);
+        const float f = fast_exp2(m_run - ((m_all == -INFINITY) ? 0.f : m_all));
+        if (c == 0) sm_l[wave * 16 + r] = l_run * f;
+        {
+            float* buf = sm_o + (wave * 16 + r) * LDS_STRIDE;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < DJ / 4; ++jj) {
+                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
+                    x *= f;
+                    *reinterpret_cast<floatx4*>(buf + (4 * c + i) * DJ + 4 * jj) = x;
+                }
+        }
+        __syncthreads();
+        float l_all = 0.f;
+#pragma unroll
+        for (int kx = 0; kx < KS; ++kx) l_all += sm_l[(kx * MB + mb) * 16 + r];
+        const int col0 = ks * SLICE + c * CPL;
+        floatx4 acc[CPL / 4];
+#pragma unroll
+        for (int qd = 0; qd < CPL / 4; ++qd) acc[qd] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kx = 0; kx < KS; ++kx) {
+            const float* buf = sm_o + ((kx * MB + mb) * 16 + r) * LDS_STRIDE + col0;
+#pragma unroll
+            for (int qd = 0; qd < CPL / 4; ++qd) acc[qd] += *reinterpret_cast<const floatx4*>(buf + 4 * qd);
+        }
+        if (p.num_splits == 1) {
+            if (row >= n_rows) return;
+            const float inv = 1.f / l_all;
+            __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head + col0;
+#pragma unroll
+            for (int qd = 0; qd < CPL / 4; ++qd)
+                *reinterpret_cast<bf16x4*>(op + 4 * qd) = __builtin_convertvector(acc[qd] * inv, bf16x4);
+            if (p.lse && c == 0 && ks == 0)
+                p.lse[(int64_t)(q0 + t_row) * p.n_q_heads + h_row] = (m_all + fast_log2(l_all)) * kLn2;
+        } else {
+            float* po = p.part_o + slot * D + col0;
+#pragma unroll
+            for (int qd = 0; qd < CPL / 4; ++qd) *reinterpret_cast<floatx4*>(po + 4 * qd) = acc[qd];
+            if (c == 0 && ks == 0) { p.part_ml[slot * 2] = m_all; p.part_ml[slot * 2 + 1] = l_all; }
         }
     }
 }
@@ -331,7 +392,7 @@ void attn_split_kernel(const AttnParams p)
 // One workgroup per (kv head, query row).  All loads of a phase are independent
 // (one split per thread for the statistics, splits strided over thread groups
 // for the outputs), so the kernel costs a few memory round trips, not one per split.
-template <int D>
+template <int D, int PRE>
 __global__ __launch_bounds__(256)
 void attn_merge_kernel(const AttnParams p)
 {
@@ -350,11 +411,21 @@ void attn_merge_kernel(const AttnParams p)
     const int64_t slot0 = (int64_t)bh * p.num_splits * p.rows_pad + row;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // phase 1: one split per thread -> global max, weights, total sum
+    // All loads are issued up front (one round trip): one split's statistics
+    // per thread, and this thread's 4 columns of up to PRE splits of its group.
+    const int grp = tid / TPR, col = (tid % TPR) * 4;
     float m_s = -INFINITY, l_s = 0.f;
     if (tid < live) {
         const float* ml = p.part_ml + (slot0 + (int64_t)tid * p.rows_pad) * 2;
         m_s = ml[0]; l_s = ml[1];
+    }
+    floatx4 ov[PRE > 0 ? PRE : 1];
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const int s = grp + GROUPS * i;
+        ov[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (s < live)
+            ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + (slot0 + (int64_t)s * p.rows_pad) * D + col);
     }
     float m = m_s;
 #pragma unroll
@@ -372,10 +443,13 @@ void attn_merge_kernel(const AttnParams p)
     __syncthreads();
     l = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
 
-    // phase 2: group `grp` accumulates splits grp, grp+GROUPS, ... for 4 columns
-    const int grp = tid / TPR, col = (tid % TPR) * 4;
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = grp; s < live; s += GROUPS)
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const int s = grp + GROUPS * i;
+        if (s < live) acc += s_w[s] * ov[i];
+    }
+    for (int s = grp + GROUPS * PRE; s < live; s += GROUPS)
         acc += s_w[s] * *reinterpret_cast<const floatx4*>(
                             p.part_o + (slot0 + (int64_t)s * p.rows_pad) * D + col);
     *reinterpret_cast<floatx4*>(&s_acc[grp][col]) = acc;
@@ -391,13 +465,14 @@ void attn_merge_kernel(const AttnParams p)
         p.lse[(int64_t)(q0 + t) * p.n_q_heads + h] = (m + fast_log2(l)) * kLn2;
 }
 
+// ---------------------------------------------------------------- host side ----
 static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
 {
-    const int max_by_len = (kv_len + kAttnWaves * kTileKeys - 1) / (kAttnWaves * kTileKeys);
+    const int max_by_len = (kv_len + 127) / 128;              // at least two tiles per split
     int s = num_splits;
     if (s <= 0) {
         const int heads = batch * n_kv_heads;
-        s = (kNumCu + heads - 1) / heads;
+        s = (kNumCu + heads - 1) / heads;                     // one workgroup per CU
     }
     if (s > max_by_len) s = max_by_len;
     if (s > kMaxSplits) s = kMaxSplits;
@@ -405,27 +480,23 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
     return s;
 }
 
-static size_t attn_lds_bytes(int mb, int d)
-{
-    const size_t merge = sizeof(float) * (size_t)(2 * kAttnWaves * mb * 16 + 2 * mb * 16 * (d + 4));
-    const size_t qstage = (size_t)mb * (d / 32) * kWave * 16;
-    return merge > qstage ? merge : qstage;
-}
-
-template <int D, int MB>
+template <int D, int MB, int KS, int TK, int NS>
 static int launch_attn(const AttnParams& p, hipStream_t stream)
 {
-    const size_t lds = attn_lds_bytes(MB, D);
+    constexpr int NW = MB * KS;
+    constexpr size_t ring = (size_t)NS * 2 * TK * D * 2;
+    constexpr size_t merge = KS > 1 ? sizeof(float) * (size_t)(2 * NW * 16 + NW * 16 * (D + 4)) : 0;
+    constexpr size_t lds = ring > merge ? ring : merge;
     if (lds > 64 * 1024) {
         static bool raised = false;
         if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return SPECVLM_ELAUNCH;
             raised = true;
         }
     }
-    hipLaunchKernelGGL((attn_split_kernel<D, MB>), dim3(p.n_work_padded), dim3(kAttnWaves * kWave),
+    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS>), dim3(p.n_work_padded), dim3(NW * kWave),
                        lds, stream, p);
     return launch_status();
 }
@@ -433,11 +504,13 @@ static int launch_attn(const AttnParams& p, hipStream_t stream)
 template <int D>
 static int launch_attn_d(const AttnParams& p, int mb, hipStream_t stream)
 {
+    // (key-split waves, tile keys, ring depth) per row-block count; the ring
+    // holds NS * 2 * TK * D * 2 bytes of LDS.
     switch (mb) {
-        case 1: return launch_attn<D, 1>(p, stream);
-        case 2: return launch_attn<D, 2>(p, stream);
-        case 3: return launch_attn<D, 3>(p, stream);
-        case 4: return launch_attn<D, 4>(p, stream);
+        case 1: return launch_attn<D, 1, 4, 128, 2>(p, stream);
+        case 2: return launch_attn<D, 2, 4, 128, 2>(p, stream);
+        case 3: return launch_attn<D, 3, 2, 64, 3>(p, stream);
+        case 4: return launch_attn<D, 4, 2, 64, 2>(p, stream);
     }
     return SPECVLM_EUNSUPPORTED;
 }
@@ -518,8 +591,8 @@ extern "C" int specvlm_decode_attn(
     if (rc != SPECVLM_OK) return rc;
     if (p.num_splits > 1) {
         dim3 grid(rows, batch * n_kv_heads);
-        if (head_dim == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, grid, dim3(256), 0, s, p);
-        else                 hipLaunchKernelGGL(attn_merge_kernel<64>, grid, dim3(256), 0, s, p);
+        if (head_dim == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 4>), grid, dim3(256), 0, s, p);
+        else                 hipLaunchKernelGGL((attn_merge_kernel<64, 4>), grid, dim3(256), 0, s, p);
         rc = launch_status();
     }
     return rc;

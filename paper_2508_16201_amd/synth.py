@@ -220,9 +220,11 @@ def make_scores(n_video: int, seed: int, *, levels: int = 0, heavy_frac: float =
 # Acceptance inputs
 # --------------------------------------------------------------------------
 def make_accept_inputs(batch: int, gamma: int, vocab: int, seed: int, *,
-                       sigma: float = 1.3, greedy: bool = True,
+                       sigma: float = 0.3, greedy: bool = True,
                        temperature: float = 1.0) -> Dict[str, np.ndarray]:
-    """Target logits ~ 3 N(0,1); draft logits = target + sigma N(0,1).
+    """Target logits ~ 3 N(0,1); draft logits = target + sigma N(0,1) (sigma 0.3:
+    the draft's argmax equals the target's about 80 % of the time, i.e. about 3.7
+    tokens per step at gamma 5, the regime of the paper's tau = 3.48).
     Draft tokens are the draft row's argmax (greedy) or drawn from the draft's
     own distribution with the generator (sampling).  Uniforms in [0,1) fp32."""
     rng = np.random.Generator(np.random.PCG64(seed))
