@@ -13,19 +13,35 @@
 //   final   scores = beta*scores + mean over (h, i), summing the kv-head / split
 //           partials in a fixed order (deterministic, no float atomics).
 //
-// Both passes are one kernel: a workgroup keeps 256 "stationary" vectors (rows
-// of Q in pass A, video keys in pass B) as MFMA B-operand fragments in
-// registers (64 per wave) and streams the other side through LDS in 64-vector
-// tiles (XOR-swizzled 16-byte chunks, double buffered).  In the accumulator
-// layout the stationary vector is lane column r and the streamed vectors are
-// rows 4c..4c+3, so each pass reduces over its streamed side inside a lane.
+// Both passes are one kernel template.  A workgroup (4 waves) keeps 256
+// "stationary" vectors (rows of Q in pass A, video keys in pass B) as MFMA
+// B-operand fragments in registers, 64 per wave, and streams the other side
+// through an LDS ring of 64-vector tiles filled by direct-to-LDS loads
+// (XOR-swizzled 16-byte chunks).  In the accumulator layout the stationary
+// vector is lane column r and the streamed vectors are rows 4c..4c+3, so each
+// pass reduces over its streamed side inside a lane and needs no cross-lane
+// traffic until the very end.
+//
+// Rows of one kv head are indexed sigma = gl * L_pad + i (q head gl of the
+// group, text query i, L_pad = L rounded up to the tile size): a streamed tile
+// of pass B therefore holds 64 consecutive queries of ONE q head and its
+// addresses need no per-lane division.
+//
+// The exponentials dominate the arithmetic (one v_exp_f32 per logit, quarter
+// rate); pass A keeps them to one per logit by rescaling its running sum only
+// when a tile's maximum exceeds the reference by more than 2^8.
 #include "common.h"
 
 namespace specvlm {
 
+#define SPECVLM_AS1 __attribute__((address_space(1)))
+#define SPECVLM_AS3 __attribute__((address_space(3)))
+
 constexpr int kScoreTile = 64;         // streamed vectors per LDS tile
 constexpr int kScoreBlock = 256;       // stationary vectors per workgroup
+constexpr int kScoreStages = 3;        // LDS ring depth
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
+constexpr float kLazyMargin = 8.f;     // log2 units of headroom before the running sum is rescaled
 
 struct ScoreParams {
     const __bf16* q;
@@ -34,7 +50,8 @@ struct ScoreParams {
     int n_text, n_keys, video_start, n_video, text_pos0;
     int n_q_heads, n_kv_heads, group;
     float scale_log2;
-    int rows, rows_pad;            // rows = n_text * group (per kv head), padded to 256
+    int l_pad;                     // n_text rounded up to the tile size
+    int rows, rows_pad;            // rows = group * l_pad (per kv head), padded to 256
     int video_pad;                 // n_video padded to 256
     int key_lo, key_hi;            // normalisation domain [key_lo, key_hi)
     int a_splits, a_split_keys;
@@ -48,17 +65,24 @@ struct ScoreParams {
     float* scores;
 };
 
+constexpr int score_vmcnt_imm(int n)
+{
+    return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8);
+}
+
 template <int D, int MODE>
 __global__ __launch_bounds__(256)
 void score_sweep_kernel(const ScoreParams p)
 {
     constexpr int KK = D / 32;
-    constexpr int CH = D / 8;                  // 16-byte chunks per vector
-    constexpr int TILE_BYTES = kScoreTile * D * 2;
-    constexpr int LOADS = kScoreTile * CH / 256;   // chunks per thread per tile
-    __shared__ __align__(16) unsigned char s_tile[2][TILE_BYTES];
-    __shared__ __align__(16) float s_lse[2][kScoreTile];
-    __shared__ int s_lim[2][kScoreTile];
+    constexpr int CH = D / 8;                        // 16-byte chunks per vector
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int TILE_BYTES = kScoreTile * ROW_BYTES;
+    constexpr int VEC_PER_LOAD = kWave / CH;         // vectors one wave-wide load covers
+    constexpr int LPW = kScoreTile / VEC_PER_LOAD / 4;   // loads per wave per tile (4 waves)
+    constexpr int NS = kScoreStages;
+    __shared__ __align__(16) unsigned char s_tile[NS][TILE_BYTES];
+    __shared__ __align__(16) float s_lse[NS][kScoreTile];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -66,7 +90,7 @@ void score_sweep_kernel(const ScoreParams p)
     const int g = blockIdx.y, split = blockIdx.z;
     const int stat0 = blockIdx.x * kScoreBlock + wave * 64;      // this wave's first stationary vector
 
-    // streamed range of this workgroup
+    // streamed range of this workgroup (multiples of the tile size)
     int s_begin, s_end;
     if (MODE == 0) {
         s_begin = p.key_lo + split * p.a_split_keys;
@@ -86,9 +110,9 @@ void score_sweep_kernel(const ScoreParams p)
         const __bf16* src = nullptr;
         lim[sb] = -1; key_abs[sb] = 0x7fffffff;
         if (MODE == 0) {
-            if (item < p.rows) {
-                const int i = item / p.group, h = g * p.group + item % p.group;
-                src = p.q + (int64_t)i * p.q_tok + (int64_t)h * p.q_head;
+            const int gl = item / p.l_pad, i = item % p.l_pad;
+            if (item < p.rows && i < p.n_text) {
+                src = p.q + (int64_t)i * p.q_tok + (int64_t)(g * p.group + gl) * p.q_head;
                 lim[sb] = p.text_pos0 + i;
             }
         } else {
@@ -105,119 +129,142 @@ void score_sweep_kernel(const ScoreParams p)
         }
     }
 
-    float m_run[4], l_run[4], col[4];
+    float m_ref[4], l_run[4], col[4];
 #pragma unroll
-    for (int sb = 0; sb < 4; ++sb) { m_run[sb] = kNegBig; l_run[sb] = 0.f; col[sb] = 0.f; }
+    for (int sb = 0; sb < 4; ++sb) { m_ref[sb] = kNegBig; l_run[sb] = 0.f; col[sb] = 0.f; }
 
-    // ---- streamed tiles: global -> registers -> swizzled LDS ----
-    u32x4 stage[LOADS];
-    float stage_lse = 0.f; int stage_lim = 0;
-    auto fetch = [&](int first) {
+    // ---- loader: direct-to-LDS, load j of a wave covers VEC_PER_LOAD vectors ----
+    const int ld_vec = lane / CH, ld_chunk = lane % CH;
+    auto issue_tile = [&](int tile, int stage) {
+        const int first = s_begin + tile * kScoreTile;
+        // pass B: the tile holds consecutive text queries of one q head
+        int gl = 0, i0 = 0;
+        if (MODE == 1) { gl = first / p.l_pad; i0 = first % p.l_pad; }
 #pragma unroll
-        for (int n = 0; n < LOADS; ++n) {
-            const int id = tid + 256 * n, it = id / CH, x = id % CH;
-            const int item = first + it;
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (item < s_end) {
-                const __bf16* src;
-                if (MODE == 0) src = p.k + (int64_t)item * p.k_tok + (int64_t)g * p.k_head;
-                else {
-                    const int i = item / p.group, h = g * p.group + item % p.group;
-                    src = p.q + (int64_t)i * p.q_tok + (int64_t)h * p.q_head;
-                }
-                raw = *reinterpret_cast<const u32x4*>(src + x * 8);
+        for (int j = 0; j < LPW; ++j) {
+            const int n = wave + 4 * j;                          // load index inside the tile
+            const int it = n * VEC_PER_LOAD + ld_vec;            // vector inside the tile
+            const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+            const int chunk = ld_chunk ^ swz;
+            const __bf16* src;
+            if (MODE == 0) {
+                const int key = min(first + it, p.n_keys - 1);   // rows past the range are masked later
+                src = p.k + (int64_t)key * p.k_tok + (int64_t)g * p.k_head;
+            } else {
+                const int i = min(i0 + it, p.n_text - 1);        // padded rows carry lse = +inf
+                src = p.q + (int64_t)i * p.q_tok + (int64_t)(g * p.group + gl) * p.q_head;
             }
-            stage[n] = raw;
+            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(src + chunk * 8),
+                                             (SPECVLM_AS3 void*)(&s_tile[stage][n * 1024]), 16, 0, 0);
         }
-        if (MODE == 1 && tid < kScoreTile) {
-            const int item = first + tid;
-            const bool ok = item < s_end;
-            stage_lse = ok ? p.lse2[(int64_t)g * p.rows_pad + item] : INFINITY;
-            stage_lim = ok ? p.text_pos0 + item / p.group : 0x7fffffff;
+        if (MODE == 1 && wave == 0) {
+            // the tile's 64 row normalisers (+inf for padded rows), one dword per lane
+            const float* src = p.lse2 + (int64_t)g * p.rows_pad + first + lane;
+            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src,
+                                             (SPECVLM_AS3 void*)(&s_lse[stage][0]), 4, 0, 0);
         }
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < LOADS; ++n) {
-            const int id = tid + 256 * n, it = id / CH, x = id % CH;
-            *reinterpret_cast<u32x4*>(&s_tile[buf][it * (D * 2) + ((x ^ (it & (CH - 1))) * 16)]) = stage[n];
-        }
-        if (MODE == 1 && tid < kScoreTile) { s_lse[buf][tid] = stage_lse; s_lim[buf][tid] = stage_lim; }
     };
 
-    auto compute = [&](int buf, int first) {
-        // pass A: does any (row, key) pair of this tile need the causal / range mask?
+    auto compute = [&](int stage, int first) {
         bool mask = false;
         if (MODE == 0) {
-            const int row_lo = blockIdx.x * kScoreBlock;          // earliest row of the workgroup
-            const int lim_lo = p.text_pos0 + row_lo / p.group;
-            mask = (first + kScoreTile > s_end) || (first + kScoreTile - 1 > lim_lo);
+            // earliest text query among the workgroup's rows sees keys <= text_pos0
+            mask = (first + kScoreTile > s_end) || (first + kScoreTile - 1 > p.text_pos0);
         }
-#pragma unroll
+#pragma unroll 1
         for (int sub = 0; sub < 4; ++sub) {
             bf16x8 af[KK];
             const int it = sub * 16 + r;
+            const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
                 const int x = kk * 4 + c;
                 af[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                    &s_tile[buf][it * (D * 2) + ((x ^ (it & (CH - 1))) * 16)]));
+                    &s_tile[stage][it * ROW_BYTES + ((x ^ swz) * 16)]));
             }
-            floatx4 lse4 = {0.f, 0.f, 0.f, 0.f};
-            int lim4[4] = {0, 0, 0, 0};
-            if (MODE == 1) {
-                lse4 = *reinterpret_cast<const floatx4*>(&s_lse[buf][sub * 16 + 4 * c]);
-                if (p.b_needs_mask) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) lim4[i] = s_lim[buf][sub * 16 + 4 * c + i];
-                }
-            }
+            floatx4 acc[4];
 #pragma unroll
             for (int sb = 0; sb < 4; ++sb) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                acc[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) acc = mfma16(af[kk], sf[sb][kk], acc);
-                if (MODE == 0) {
-                    float s[4];
+                for (int kk = 0; kk < KK; ++kk) acc[sb] = mfma16(af[kk], sf[sb][kk], acc[sb]);
+            }
+            if (MODE == 0) {
+                float tmax[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        s[i] = acc[i] * p.scale_log2;
-                        if (mask) {
+                for (int sb = 0; sb < 4; ++sb) {
+                    acc[sb] *= p.scale_log2;
+                    if (mask) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
                             const int key = first + sub * 16 + 4 * c + i;
-                            if (key >= s_end || key > lim[sb]) s[i] = -INFINITY;
+                            if (key >= s_end || key > lim[sb]) acc[sb][i] = -INFINITY;
                         }
                     }
-                    const float m_new = fmaxf(fmaxf(m_run[sb], fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
-                    const float sum = (fast_exp2(s[0] - m_new) + fast_exp2(s[1] - m_new)) +
-                                      (fast_exp2(s[2] - m_new) + fast_exp2(s[3] - m_new));
-                    l_run[sb] = l_run[sb] * fast_exp2(m_run[sb] - m_new) + sum;
-                    m_run[sb] = m_new;
-                } else {
-                    float sum = 0.f;
+                    tmax[sb] = fmaxf(fmaxf(acc[sb][0], acc[sb][1]), fmaxf(acc[sb][2], acc[sb][3]));
+                }
+                // rescale only when some row's new maximum outgrows its reference
+                bool grow = false;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float pr = fast_exp2(acc[i] * p.scale_log2 - lse4[i]);
-                        if (p.b_needs_mask && key_abs[sb] > lim4[i]) pr = 0.f;
-                        sum += pr;
+                for (int sb = 0; sb < 4; ++sb) grow = grow || (tmax[sb] > m_ref[sb] + kLazyMargin);
+                if (__any(grow)) {
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        const float m_new = fmaxf(m_ref[sb], tmax[sb]);
+                        l_run[sb] *= fast_exp2(m_ref[sb] - m_new);
+                        m_ref[sb] = m_new;
                     }
-                    col[sb] += sum;
+                }
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb) {
+                    const float sum = (fast_exp2(acc[sb][0] - m_ref[sb]) + fast_exp2(acc[sb][1] - m_ref[sb])) +
+                                      (fast_exp2(acc[sb][2] - m_ref[sb]) + fast_exp2(acc[sb][3] - m_ref[sb]));
+                    l_run[sb] += sum;
+                }
+            } else {
+                const floatx4 lse4 = *reinterpret_cast<const floatx4*>(&s_lse[stage][sub * 16 + 4 * c]);
+                if (p.b_needs_mask) {
+                    // text query i of this tile sees keys <= text_pos0 + i
+                    const int lim0 = p.text_pos0 + (first % p.l_pad) + sub * 16 + 4 * c;
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float pr = fast_exp2(acc[sb][i] * p.scale_log2 - lse4[i]);
+                            sum += (key_abs[sb] > lim0 + i) ? 0.f : pr;
+                        }
+                        col[sb] += sum;
+                    }
+                } else {
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb) {
+                        const float sum = (fast_exp2(acc[sb][0] * p.scale_log2 - lse4[0]) +
+                                           fast_exp2(acc[sb][1] * p.scale_log2 - lse4[1])) +
+                                          (fast_exp2(acc[sb][2] * p.scale_log2 - lse4[2]) +
+                                           fast_exp2(acc[sb][3] * p.scale_log2 - lse4[3]));
+                        col[sb] += sum;
+                    }
                 }
             }
         }
     };
 
+    // ---- ring: NS-1 tiles in flight while one is consumed; one barrier per tile ----
     const int n_tiles = (s_end - s_begin + kScoreTile - 1) / kScoreTile;
-    if (n_tiles > 0) {
-        fetch(s_begin);
-        commit(0);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < n_tiles) issue_tile(s, s);
     for (int t = 0; t < n_tiles; ++t) {
-        const bool more = t + 1 < n_tiles;
-        if (more) fetch(s_begin + (t + 1) * kScoreTile);
-        compute(t & 1, s_begin + t * kScoreTile);
-        if (more) commit((t + 1) & 1);
-        __syncthreads();
+        const int younger = min(NS - 2, n_tiles - 1 - t);
+        // (wave 0 of pass B has one more load per tile: it waits slightly longer than needed)
+        if (younger >= 1) __builtin_amdgcn_s_waitcnt(score_vmcnt_imm(LPW) & ~(15 << 8));
+        else __builtin_amdgcn_s_waitcnt(score_vmcnt_imm(0) & ~(15 << 8));
+        __asm__ volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __asm__ volatile("" ::: "memory");
+        if (t + NS - 1 < n_tiles) issue_tile(t + NS - 1, (t + NS - 1) % NS);
+        compute(t % NS, s_begin + t * kScoreTile);
     }
 
     // ---- reduce over the four lane groups that share a stationary vector ----
@@ -225,7 +272,7 @@ void score_sweep_kernel(const ScoreParams p)
     for (int sb = 0; sb < 4; ++sb) {
         const int item = stat0 + sb * 16 + r;
         if (MODE == 0) {
-            float m = m_run[sb], l = l_run[sb];
+            float m = m_ref[sb], l = l_run[sb];
 #pragma unroll
             for (int off = 16; off <= 32; off <<= 1) {
                 const float om = __shfl_xor(m, off), ol = __shfl_xor(l, off);
@@ -254,10 +301,10 @@ void score_lse_kernel(const ScoreParams p)
     const int row = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
     if (row >= p.rows_pad) return;
     float out = INFINITY;                       // padded / keyless rows contribute nothing
-    if (row < p.rows) {
+    const int gl = row / p.l_pad, i = row % p.l_pad;
+    if (row < p.rows && i < p.n_text) {
         if (p.row_lse) {
-            const int i = row / p.group, h = g * p.group + row % p.group;
-            out = p.row_lse[(int64_t)i * p.n_q_heads + h] * kLog2e;
+            out = p.row_lse[(int64_t)i * p.n_q_heads + g * p.group + gl] * kLog2e;
             if (!(out > -INFINITY)) out = INFINITY;
         } else {
             const float* src = p.part_ml + ((int64_t)g * p.rows_pad + row) * p.a_splits * 2;
@@ -284,7 +331,7 @@ void score_final_kernel(const ScoreParams p)
 }
 
 struct ScorePlan {
-    int rows, rows_pad, video_pad, key_lo, key_hi, a_splits, a_split_keys, b_splits, b_split_rows;
+    int l_pad, rows, rows_pad, video_pad, key_lo, key_hi, a_splits, a_split_keys, b_splits, b_split_rows;
     size_t off_ml, off_lse, off_cols, total;
 };
 
@@ -293,12 +340,13 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
 {
     ScorePlan s;
     const int group = n_q_heads / n_kv_heads;
-    s.rows = n_text * group;
-    s.rows_pad = round_up(s.rows > 0 ? s.rows : 1, kScoreBlock);
+    s.l_pad = round_up(n_text > 0 ? n_text : 1, kScoreTile);
+    s.rows = group * s.l_pad;
+    s.rows_pad = round_up(s.rows, kScoreBlock);
     s.video_pad = round_up(n_video > 0 ? n_video : 1, kScoreBlock);
     s.key_lo = norm_mode ? video_start : 0;
     s.key_hi = norm_mode ? video_start + n_video : n_keys;
-    const int target_wgs = 2 * kNumCu;
+    const int target_wgs = 3 * kNumCu;
     const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
     const int dom = s.key_hi - s.key_lo;
     int a = (target_wgs + blocks_a - 1) / blocks_a;
@@ -314,8 +362,8 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
     if (b > b_max) b = b_max;
     if (b > 16) b = 16;
     if (b < 1) b = 1;
-    s.b_split_rows = round_up((s.rows + b - 1) / b > 0 ? (s.rows + b - 1) / b : 1, kScoreTile);
-    s.b_splits = s.rows > 0 ? (s.rows + s.b_split_rows - 1) / s.b_split_rows : 1;
+    s.b_split_rows = round_up((s.rows + b - 1) / b, kScoreTile);
+    s.b_splits = (s.rows + s.b_split_rows - 1) / s.b_split_rows;
     size_t off = 0;
     s.off_ml = off;
     if (!have_row_lse) off += align256((size_t)n_kv_heads * s.rows_pad * s.a_splits * 2 * sizeof(float));
@@ -377,6 +425,7 @@ extern "C" int specvlm_score(
     p.text_pos0 = text_pos0;
     p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = n_q_heads / n_kv_heads;
     p.scale_log2 = softmax_scale * kLog2e;
+    p.l_pad = plan.l_pad;
     p.rows = plan.rows; p.rows_pad = plan.rows_pad; p.video_pad = plan.video_pad;
     p.key_lo = plan.key_lo; p.key_hi = plan.key_hi;
     p.a_splits = plan.a_splits; p.a_split_keys = plan.a_split_keys;
