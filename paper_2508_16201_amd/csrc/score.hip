@@ -346,24 +346,31 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
     s.video_pad = round_up(n_video > 0 ? n_video : 1, kScoreBlock);
     s.key_lo = norm_mode ? video_start : 0;
     s.key_hi = norm_mode ? video_start + n_video : n_keys;
-    const int target_wgs = 3 * kNumCu;
-    const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
+    // Three workgroups fit a CU (48 KB of LDS ring, < 170 VGPRs).  A split count is
+    // good when the workgroups fill whole rounds of those slots: minimise
+    // rounds x tiles-per-workgroup, ties to the fewer splits (less partial traffic).
+    const int slots = 3 * kNumCu;
+    auto best_splits = [&](int blocks, int streamed, int max_splits, int* per_split) {
+        int best = 1, best_per = round_up(streamed > 0 ? streamed : 1, kScoreTile);
+        long best_cost = -1;
+        for (int n = 1; n <= max_splits; ++n) {
+            const int per = round_up((streamed + n - 1) / n > 0 ? (streamed + n - 1) / n : 1, kScoreTile);
+            const int live = streamed > 0 ? (streamed + per - 1) / per : 1;
+            if (live != n) continue;                             // same partition as a smaller n
+            const long wgs = (long)blocks * live;
+            const long rounds = (wgs + slots - 1) / slots;
+            // +2 tiles: a workgroup's fixed cost (stationary fragments, ring fill); + live: fewer splits on ties
+            const long cost = rounds * (per / kScoreTile + 2) * 64 + live;
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = live; best_per = per; }
+        }
+        *per_split = best_per;
+        return best;
+    };
     const int dom = s.key_hi - s.key_lo;
-    int a = (target_wgs + blocks_a - 1) / blocks_a;
-    const int a_max = (dom + 4 * kScoreTile - 1) / (4 * kScoreTile);       // >= 4 tiles per split
-    if (a > a_max) a = a_max;
-    if (a > 64) a = 64;
-    if (a < 1) a = 1;
-    s.a_split_keys = round_up((dom + a - 1) / a > 0 ? (dom + a - 1) / a : 1, kScoreTile);
-    s.a_splits = dom > 0 ? (dom + s.a_split_keys - 1) / s.a_split_keys : 1;
+    const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
+    s.a_splits = best_splits(blocks_a, dom, 64, &s.a_split_keys);
     const int blocks_b = (s.video_pad / kScoreBlock) * n_kv_heads;
-    int b = (target_wgs + blocks_b - 1) / blocks_b;
-    const int b_max = (s.rows + 4 * kScoreTile - 1) / (4 * kScoreTile);
-    if (b > b_max) b = b_max;
-    if (b > 16) b = 16;
-    if (b < 1) b = 1;
-    s.b_split_rows = round_up((s.rows + b - 1) / b, kScoreTile);
-    s.b_splits = (s.rows + s.b_split_rows - 1) / s.b_split_rows;
+    s.b_splits = best_splits(blocks_b, s.rows, 16, &s.b_split_rows);
     size_t off = 0;
     s.off_ml = off;
     if (!have_row_lse) off += align256((size_t)n_kv_heads * s.rows_pad * s.a_splits * 2 * sizeof(float));
