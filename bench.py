@@ -27,6 +27,10 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per verify-attention launch (split + merge) from the rocprofv3 PMC runs summarised in
+# profiles/bench_72b-full_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE, scaled by the copy-kernel factors).
+# Only valid for the default launch shape of that workload.
+MEASURED_TRAFFIC_BYTES = {("72b-full", "head-major", 0): 66.0e6}
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -253,7 +257,8 @@ def main():
         "n_accepted": int(n_acc.item()),
         "roofline": {"kernel": "specvlm_decode_attn (verify, split + merge)", "bound": "hbm",
                      "achieved": round(attn_gbs2, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(attn_gbs2 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(attn_gbs2 / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.layout, args.num_splits)),
                      "algorithmic_bytes_per_launch": attn_bytes},
     }
 

@@ -191,7 +191,9 @@ void attn_split_kernel(const AttnParams p)
             const int n = wave + LW * j;
             const bool is_v = n >= LOADS_PER_MAT;
             const int kl = (is_v ? n - LOADS_PER_MAT : n) * KEYS_PER_LOAD + ld_key;   // key inside the tile
-            const uint32_t key = (uint32_t)min(base + kl, kvl - 1);
+            // rows past the split's end are masked in the compute: re-read its last row
+            // (a cache hit) instead of pulling the neighbour split's keys from HBM
+            const uint32_t key = (uint32_t)min(base + kl, k_end - 1);
             // K rows are chunk-swizzled so operand reads spread over the banks
             const int swz = (D == 128) ? (kl & 15) : ((kl >> 1) & 7);
             const int chunk = is_v ? ld_chunk : (ld_chunk ^ swz);

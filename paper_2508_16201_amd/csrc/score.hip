@@ -87,8 +87,17 @@ void score_sweep_kernel(const ScoreParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, c = lane >> 4;
-    const int g = blockIdx.y, split = blockIdx.z;
-    const int stat0 = blockIdx.x * kScoreBlock + wave * 64;      // this wave's first stationary vector
+    // Workgroups go to the XCDs round-robin by linear id.  Decode the id so that
+    // the stationary blocks of one (kv head, split) are neighbours on ONE XCD:
+    // they stream the same tiles at the same time and share them in that L2.
+    const int n_blocks = (MODE == 0 ? p.rows_pad : p.video_pad) / kScoreBlock;
+    const int n_split = (MODE == 0 ? p.a_splits : p.b_splits);
+    const int vid = xcd_logical_id(blockIdx.x, gridDim.x);
+    if (vid >= n_blocks * n_split * p.n_kv_heads) return;
+    const int blk = vid % n_blocks;
+    const int split = (vid / n_blocks) % n_split;
+    const int g = vid / (n_blocks * n_split);
+    const int stat0 = blk * kScoreBlock + wave * 64;             // this wave's first stationary vector
 
     // streamed range of this workgroup (multiples of the tile size)
     int s_begin, s_end;
@@ -449,12 +458,12 @@ extern "C" int specvlm_score(
 
     if (n_text > 0) {
         if (!row_lse && p.key_hi > p.key_lo) {
-            dim3 grid(plan.rows_pad / kScoreBlock, n_kv_heads, plan.a_splits);
+            dim3 grid(round_up((plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits, kNumXcd));
             if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 0>), grid, dim3(256), 0, s, p);
             else                 hipLaunchKernelGGL((score_sweep_kernel<64, 0>), grid, dim3(256), 0, s, p);
         }
         hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads), dim3(256), 0, s, p);
-        dim3 grid(plan.video_pad / kScoreBlock, n_kv_heads, plan.b_splits);
+        dim3 grid(round_up((plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits, kNumXcd));
         if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 1>), grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL((score_sweep_kernel<64, 1>), grid, dim3(256), 0, s, p);
     } else {
