@@ -46,6 +46,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sampling", action="store_true", help="rejection-sampling accept instead of greedy")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying HIP graphs")
+    ap.add_argument("--frames", type=int, default=0, help="override the frame count (with --attn-only)")
+    ap.add_argument("--attn-only", action="store_true",
+                    help="time only the verify attention of --workload (32b-long, ragged-x8, ...): extra context "
+                         "numbers, not the headline line")
     return ap.parse_args()
 
 
@@ -61,6 +65,8 @@ def main():
 
     B.lib()                                    # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.attn_only:
+        return attn_only(args, torch, B, synth)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = synth.WORKLOADS[args.workload]
@@ -279,6 +285,79 @@ def main():
                                   "sample": f"{passes} passes of the verify attention of layer 0 of {L} "
                                             f"(fp64 oracle, {dt:.1f} s, OpenMP over query rows)"}
     print(json.dumps(result))
+
+
+def attn_only(args, torch, B, synth):
+    """Verify attention alone on another workload: `layers` distinct caches
+    (more than the 256 MB Infinity Cache holds) replayed from one HIP graph."""
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.WORKLOADS[args.workload]
+    if args.frames:
+        w = synth.scaled(w, n_frames=args.frames)
+    hq, hkv, d, g1 = w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len
+    if w.name == "ragged-x8":
+        lens = [int(f) * 196 + w.n_text + g1 for f in synth.ragged_frames()]
+    else:
+        lens = [w.kv_len]
+    batch, total = len(lens), sum(lens)
+    attn_bytes = 2 * total * hkv * d * 2 + 2 * batch * g1 * hq * d * 2
+    layers = max(2, min(w.n_layers if w.n_layers > 1 else 8, int(1.5e9 // attn_bytes) + 1))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED_BASE + 1000 * w.index)
+
+    def randn_bf16(shape):
+        return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    # request-major, then head-major inside a request: [request][H_kv][kv_len_b][d], addressed as one
+    # [sum kv_len, H_kv, d] view needs a common head stride, so ragged batches use the token-major layout
+    if batch == 1 and args.layout == "head-major":
+        k = [randn_bf16((hkv, total, d)).permute(1, 0, 2) for _ in range(layers)]
+        v = [randn_bf16((hkv, total, d)).permute(1, 0, 2) for _ in range(layers)]
+    else:
+        k = [randn_bf16((total, hkv, d)) for _ in range(layers)]
+        v = [randn_bf16((total, hkv, d)) for _ in range(layers)]
+    q = [randn_bf16((batch * g1, hq, d)) for _ in range(layers)]
+    out = torch.empty((batch * g1, hq, d), dtype=torch.bfloat16, device=dev)
+    import numpy as np
+    cu_q = torch.tensor(np.arange(batch + 1) * g1, dtype=torch.int32, device=dev) if batch > 1 else None
+    cu_kv = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev) if batch > 1 else None
+    ws = B.new_workspace(B.decode_attn_workspace_bytes(batch, g1, max(lens), hq, hkv, d, args.num_splits), dev)
+
+    def stage():
+        for l in range(layers):
+            B.decode_attn(q[l], k[l], v[l], w.softmax_scale, cu_q=cu_q, cu_kv=cu_kv, max_q_len=g1,
+                          max_kv_len=max(lens), out=out, num_splits=args.num_splits, workspace=ws)
+
+    stage()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stage()
+    for _ in range(args.warmup):
+        graph.replay()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (args.steps * layers)
+    gbs = attn_bytes / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "verify-step attn HBM GB/s (% peak)", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * layers / 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name} (verify attention only): batch {batch}, {total} keys, {hq}/{hkv} heads "
+                               f"d{d}, gamma {w.gamma}, {layers} distinct layers",
+                   "kv_layout": args.layout if batch == 1 else "token-major",
+                   "num_splits": args.num_splits},
+        "verify_attn_us_per_layer": round(us, 2),
+        "roofline": {"kernel": "specvlm_decode_attn (verify, split + merge)", "bound": "hbm",
+                     "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": attn_bytes}}))
 
 
 if __name__ == "__main__":

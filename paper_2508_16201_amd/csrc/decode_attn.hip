@@ -53,7 +53,8 @@ struct AttnParams {
     float* part_o;           // [batch*H_kv][num_splits][rows_pad][D] unnormalised partial outputs
     float* part_ml;          // [batch*H_kv][num_splits][rows_pad][2] (running max in log2 units, sum)
     int rows_pad;
-    int n_work, n_work_padded;
+    int n_work;
+    int heads_fastest;
 };
 
 constexpr int kChunkKeys = 32;       // keys per PV contraction step
@@ -133,10 +134,22 @@ void attn_split_kernel(const AttnParams p)
     static_assert(NS >= 2 && NS <= 6, "ring depth");
     typedef typename ValueVec<D>::type vvec_t;
 
-    const int vid = xcd_logical_id(blockIdx.x, p.n_work_padded);
-    if (vid >= p.n_work) return;
-    const int split = vid % p.num_splits;
-    const int bh = vid / p.num_splits;
+    // Dispatch order.  Head-major caches: consecutive workgroups are consecutive
+    // splits of one (request, head).  Token-major caches interleave the heads
+    // inside every token row, so the kv heads of one (request, split) are made
+    // neighbours: they start together and walk the same DRAM pages at the same
+    // time.  Either way a request is spread over all XCDs (ragged batches stay
+    // balanced; the merge reads the partials through HBM anyway).
+    const int vid = blockIdx.x;
+    int split, bh;
+    if (p.heads_fastest) {
+        const int g_ = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
+        split = rest % p.num_splits;
+        bh = (rest / p.num_splits) * p.n_kv_heads + g_;
+    } else {
+        split = vid % p.num_splits;
+        bh = vid / p.num_splits;
+    }
     const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
 
     int q0 = 0, ql = p.q_len, kv0 = 0, kvl = p.kv_len;
@@ -473,8 +486,21 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
     const int max_by_len = (kv_len + 127) / 128;              // at least two tiles per split
     int s = num_splits;
     if (s <= 0) {
+        // one workgroup per CU when the (request, head) pairs are few; for many
+        // pairs (ragged batches) cap a split at 2048 keys so that long and short
+        // requests decompose into similar pieces the dispatcher can balance
         const int heads = batch * n_kv_heads;
-        s = (kNumCu + heads - 1) / heads;                     // one workgroup per CU
+        const int fill = (kNumCu + heads - 1) / heads;
+        const int by_len = (kv_len + 2047) / 2048;
+        s = fill > by_len ? fill : by_len;
+        // two workgroups are resident per CU (64 KB of LDS ring each): when the
+        // launch needs several rounds, make it a whole number of rounds
+        const int slots = 2 * kNumCu;
+        if (heads * s > slots && slots % heads == 0) {
+            const int unit = slots / heads;
+            s = ((s + unit / 2) / unit) * unit;
+            if (s < unit) s = unit;
+        }
     }
     if (s > max_by_len) s = max_by_len;
     if (s > kMaxSplits) s = kMaxSplits;
@@ -498,7 +524,7 @@ static int launch_attn(const AttnParams& p, hipStream_t stream)
             raised = true;
         }
     }
-    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS>), dim3(p.n_work_padded), dim3(NW * kWave),
+    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS>), dim3(p.n_work), dim3(NW * kWave),
                        lds, stream, p);
     return launch_status();
 }
@@ -511,7 +537,7 @@ static int launch_attn_d(const AttnParams& p, int mb, hipStream_t stream)
     switch (mb) {
         case 1: return launch_attn<D, 1, 4, 128, 2>(p, stream);
         case 2: return launch_attn<D, 2, 4, 128, 2>(p, stream);
-        case 3: return launch_attn<D, 3, 2, 64, 3>(p, stream);
+        case 3: return launch_attn<D, 3, 2, 64, 2>(p, stream);
         case 4: return launch_attn<D, 4, 2, 64, 2>(p, stream);
     }
     return SPECVLM_EUNSUPPORTED;
@@ -578,7 +604,7 @@ extern "C" int specvlm_decode_attn(
     p.split_keys = (kv_len + p.num_splits - 1) / p.num_splits;
     p.rows_pad = mb * 16;
     p.n_work = batch * n_kv_heads * p.num_splits;
-    p.n_work_padded = round_up(p.n_work, kNumXcd);
+    p.heads_fastest = (kv_tok_stride > kv_head_stride) ? 1 : 0;
     p.part_o = nullptr; p.part_ml = nullptr;
     if (p.num_splits > 1) {
         const size_t need = specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads,

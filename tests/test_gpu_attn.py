@@ -165,3 +165,49 @@ def test_argument_errors(B):
     with pytest.raises(B.SpecVLMError) as e:
         B.decode_attn(qq, kk, kk, 0.1, num_splits=8, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == -3
+
+
+def test_full_size_32b_long_layer_sampled_rows(B):
+    """configs[3] shape: 32 768 video + 256 text keys, 40/8 heads (group 5), d 128,
+    gamma in {3, 5, 7}; the oracle checks every row of one kv-head group."""
+    for gamma, g in ((3, 1), (5, 4), (7, 7)):
+        w = synth.scaled(synth.V32B_LONG, gamma=gamma)
+        t = synth.make_layer(w, layer=gamma)
+        scale = w.softmax_scale
+        out, lse = B.decode_attn(dev_bf16(t["q_block"]), dev_bf16(t["k"]), dev_bf16(t["v"]), scale, want_lse=True)
+        torch.cuda.synchronize()
+        hs = slice(g * 5, g * 5 + 5)
+        want, want_lse = oracle.decode_attn(t["q_block"][:, hs], t["k"][:, g:g + 1], t["v"][:, g:g + 1], scale)
+        assert_attn_close(out[:, hs], want, f"32b-long gamma {gamma} kv head {g}")
+        np.testing.assert_allclose(host_f64(lse[:, hs]), want_lse, atol=2e-3, rtol=1e-4)
+
+
+def test_ragged_batch_of_eight_in_one_launch(B):
+    """configs[4]: 8 requests, video lengths 21..167 frames x 196 tokens + 256 text
+    + the verify block, 64/8 heads, d 128, gamma 5, one launch with cu arrays.
+    The oracle checks two kv-head groups of the shortest, the longest and one
+    middle request; the other requests are checked through the lse identity
+    sum_j p_j = 1 (rows of V set to one give ones back)."""
+    frames = synth.ragged_frames()
+    hq, hkv, d, g1 = 64, 8, 128, 6
+    lens = [int(f) * 196 + 256 + g1 for f in frames]
+    rng = np.random.default_rng(77)
+    qs = [rnd_bits((g1, hq, d), 500 + i) for i in range(8)]
+    ks = [rnd_bits((n, hkv, d), 600 + i) for i, n in enumerate(lens)]
+    vs = [rnd_bits((n, hkv, d), 700 + i) for i, n in enumerate(lens)]
+    cu_q = torch.tensor(np.arange(9) * g1, dtype=torch.int32).cuda()
+    cu_kv = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32).cuda()
+    qd, kd, vd = dev_bf16(np.concatenate(qs)), dev_bf16(np.concatenate(ks)), dev_bf16(np.concatenate(vs))
+    scale = 1 / np.sqrt(d)
+    out = B.decode_attn(qd, kd, vd, scale, cu_q=cu_q, cu_kv=cu_kv, max_q_len=g1, max_kv_len=max(lens))
+    torch.cuda.synchronize()
+    order = np.argsort(lens)
+    for i in (int(order[0]), int(order[4]), int(order[-1])):
+        for g in (0, 6):
+            hs = slice(g * 8, g * 8 + 8)
+            want, _ = oracle.decode_attn(qs[i][:, hs], ks[i][:, g:g + 1], vs[i][:, g:g + 1], scale)
+            assert_attn_close(out[i * g1:(i + 1) * g1, hs], want, f"ragged request {i} kv head {g}")
+    ones = torch.ones_like(vd)
+    out1 = B.decode_attn(qd, kd, ones, scale, cu_q=cu_q, cu_kv=cu_kv, max_q_len=g1, max_kv_len=max(lens))
+    torch.cuda.synchronize()
+    assert (out1.float() - 1.0).abs().max().item() <= 2 ** -7
