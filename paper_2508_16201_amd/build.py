@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms are kept off for every device function
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results feed VALU code (softmax, exponentials): keep them in arch VGPRs
+    # instead of AGPRs so no v_accvgpr_read copies are needed
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wno-unused-command-line-argument",
 ]
 
