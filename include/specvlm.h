@@ -6,6 +6,7 @@
  *
  *   specvlm_score        language-to-video attention scores   (Sec. 3.1, Eq. 4-5)
  *   specvlm_select       Stage I top-k + Stage II uniform stride (Sec. 3.2, Eq. 6-7)
+ *   specvlm_top_p_count  Stage I's size by cumulative score mass (Sec. 3.2, Eq. 6)
  *   specvlm_gather_kv    the draft's pruned KV cache           (Sec. 3.2, last paragraph)
  *   specvlm_decode_attn  draft decode / parallel verification  (Sec. 2.1)
  *   specvlm_accept       draft-token acceptance                (Sec. 2.1; App. A greedy)
@@ -132,6 +133,27 @@ int specvlm_select(
     const int32_t* k_top, const int32_t* keep_budget, const int32_t* cu_keep,
     int batch, int max_n_video, int total_keep,
     int32_t* keep_idx, uint8_t* from_topk, int32_t* status,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_top_p_count -- Stage I's own size rule  (Sec. 3.2, Eq. 6): for each
+ * request, count[b] = the smallest c such that the c largest scores sum to at
+ * least lambda times the sum of all scores (0 when the total is 0 or lambda
+ * is 0), clamped to max_count[b] when max_count is given.  The result can be
+ * passed to specvlm_select as k_top (with max_count = keep_budget).
+ * Scores are attention masses: values that are not > 0 (negatives, NaN) count
+ * as 0.  Sums are exact 64-bit fixed point (2^-40 of the largest score), so the
+ * result is deterministic; it can differ from an fp64 evaluation only when
+ * lambda * total lies within ~1e-9 * total of a prefix sum.
+ *   scores fp32 [sum n_video_b]; cu_video int32 [batch+1] or NULL (batch 1);
+ *   max_count device int32 [batch] or NULL; count device int32 [batch].
+ * Limit: max_n_video <= 65536.  No workspace is needed (the query returns 0).
+ * -------------------------------------------------------------------------- */
+size_t specvlm_top_p_count_workspace_bytes(int batch, int max_n_video);
+
+int specvlm_top_p_count(
+    const float* scores, const int32_t* cu_video, int batch, int max_n_video,
+    float lambda, const int32_t* max_count, int32_t* count,
     void* workspace, size_t workspace_bytes, void* stream);
 
 /* --------------------------------------------------------------------------

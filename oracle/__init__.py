@@ -93,12 +93,13 @@ def select(scores, k_top: int, keep_budget: int) -> Tuple[np.ndarray, np.ndarray
     return keep, flag
 
 
-def top_p_count(scores, lam: float) -> int:
+def top_p_count(scores, lam: float, want_margin: bool = False):
     s = np.ascontiguousarray(scores, dtype=np.float32)
-    c = lib().oracle_top_p_count(_p(s), s.shape[0], C.c_double(lam))
+    margin = C.c_double(1.0)
+    c = lib().oracle_top_p_count(_p(s), s.shape[0], C.c_double(lam), C.byref(margin))
     if c < 0:
         raise ValueError(f"oracle_top_p_count rc={c}")
-    return c
+    return (c, margin.value) if want_margin else c
 
 
 def gather_kv(src, video_start: int, n_video: int, keep_idx) -> np.ndarray:

@@ -219,10 +219,12 @@ int oracle_select(const float* scores, int n_video, int k_top, int keep_budget,
 
 /* Stage I's own size rule (Eq. 6): the smallest c such that the c largest
  * scores sum to at least lambda times the total.  Sums in fp64 in sorted
- * order.  Returns c, or a negative error. */
-int oracle_top_p_count(const float* scores, int n_video, double lambda)
+ * order.  Returns c, or a negative error.  *margin (optional) receives the distance
+ * of lambda*total to the nearer of the two prefix sums that decide c, divided by the total. */
+int oracle_top_p_count(const float* scores, int n_video, double lambda, double* margin)
 {
     if (n_video < 0 || !(lambda >= 0.0 && lambda <= 1.0)) return -1;
+    if (margin) *margin = 1.0;
     if (n_video == 0) return 0;
     scored_t* order = (scored_t*)malloc(sizeof(scored_t) * (size_t)n_video);
     if (!order) return -2;
@@ -232,9 +234,16 @@ int oracle_top_p_count(const float* scores, int n_video, double lambda)
         total += (double)scores[j];
     }
     qsort(order, (size_t)n_video, sizeof(scored_t), cmp_desc);
-    double acc = 0.0;
+    double acc = 0.0, before = 0.0;
     int c = 0;
-    while (c < n_video && !(acc >= lambda * total)) { acc += (double)order[c].key; ++c; }
+    while (c < n_video && !(acc >= lambda * total)) { before = acc; acc += (double)order[c].key; ++c; }
+    /* margin: how far the threshold sits from the two partial sums that decide c, relative to the total */
+    if (margin && total > 0.0) {
+        const double goal = lambda * total;
+        const double d_hi = acc - goal;                       /* >= 0 when the loop stopped on the test */
+        const double d_lo = c > 0 ? goal - before : goal;     /* > 0: the previous prefix fell short */
+        *margin = (d_hi < d_lo ? d_hi : d_lo) / total;
+    }
     free(order);
     return c;
 }

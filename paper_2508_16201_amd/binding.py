@@ -21,6 +21,7 @@ EXPORTS = (
     "specvlm_status_string", "specvlm_version",
     "specvlm_score_workspace_bytes", "specvlm_score",
     "specvlm_select_workspace_bytes", "specvlm_select",
+    "specvlm_top_p_count_workspace_bytes", "specvlm_top_p_count",
     "specvlm_gather_kv",
     "specvlm_decode_attn_workspace_bytes", "specvlm_decode_attn",
     "specvlm_accept_workspace_bytes", "specvlm_accept",
@@ -55,6 +56,8 @@ def lib() -> C.CDLL:
                                     i32, vp, f32, vp, vp, sz, vp]
         l.specvlm_select_workspace_bytes.argtypes = [i32, i32]
         l.specvlm_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        l.specvlm_top_p_count_workspace_bytes.argtypes = [i32, i32]
+        l.specvlm_top_p_count.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, sz, vp]
         l.specvlm_gather_kv.argtypes = [vp, vp, i64, i64, i64, vp, vp, i64, i64, i64,
                                         i32, i32, i32, i32, vp, i32, i32, i32, vp]
         l.specvlm_decode_attn_workspace_bytes.argtypes = [i32] * 7
@@ -62,7 +65,7 @@ def lib() -> C.CDLL:
                                           i32, i32, i32, f32, vp, vp, i32, vp, sz, vp]
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
-        for name in ("specvlm_score", "specvlm_select", "specvlm_gather_kv",
+        for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
                      "specvlm_decode_attn", "specvlm_accept"):
             getattr(l, name).restype = C.c_int
         _lib = l
@@ -164,6 +167,23 @@ def select(scores: torch.Tensor, k_top: torch.Tensor, keep_budget: torch.Tensor,
     _check("specvlm_select", rc)
     out = (keep_idx, flags)
     return out + (status,) if want_status else out
+
+
+def top_p_count(scores: torch.Tensor, lam: float, *, cu_video: Optional[torch.Tensor] = None,
+                max_n_video: Optional[int] = None, max_count: Optional[torch.Tensor] = None,
+                count: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores fp32 [sum V_b] -> count int32 [batch]: Eq. 6's retention size per request."""
+    batch = 1 if cu_video is None else cu_video.numel() - 1
+    if max_n_video is None:
+        if cu_video is not None:
+            raise ValueError("max_n_video is required with cu_video")
+        max_n_video = scores.numel()
+    if count is None:
+        count = torch.empty(batch, dtype=torch.int32, device=scores.device)
+    rc = lib().specvlm_top_p_count(_ptr(scores), _ptr(cu_video), batch, max_n_video, float(lam),
+                                   _ptr(max_count), _ptr(count), None, 0, _stream())
+    _check("specvlm_top_p_count", rc)
+    return count
 
 
 # ----------------------------------------------------------------------- gather_kv

@@ -213,6 +213,166 @@ void select_kernel(const SelectParams p)
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Stage I's own size rule (Sec. 3.2, Eq. 6): the smallest c such that the c
+// largest scores reach lambda of the total score mass.  Same radix descent as
+// the selection, but the per-digit histograms carry SUMS as well as counts.
+// Sums are 64-bit fixed point (score * 2^40 / max score): integer adds commute,
+// so the result does not depend on the order in which lanes reach the atomics.
+// Scores are attention masses (>= 0); negative values and NaN count as 0.
+struct TopPParams {
+    const float* scores;
+    const int32_t* cu_video;
+    int max_n_video;
+    float lambda;
+    const int32_t* max_count;
+    int32_t* count;
+};
+
+template <int E>
+__global__ __launch_bounds__(kSelThreads)
+void top_p_kernel(const TopPParams p)
+{
+    __shared__ int s_cnt[kSelWaves][256];
+    __shared__ unsigned long long s_sum[kSelWaves][256];
+    __shared__ int s_tcnt[256];
+    __shared__ unsigned long long s_tsum[256];
+    __shared__ float s_redf[kSelWaves];
+    __shared__ unsigned long long s_redu[kSelWaves];
+    __shared__ unsigned long long s_pick_sum;
+    __shared__ int s_pick[3];
+
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int v0 = p.cu_video ? p.cu_video[b] : 0;
+    const int n = p.cu_video ? p.cu_video[b + 1] - v0 : p.max_n_video;
+    if (n <= 0 || n > E * kSelThreads) { if (tid == 0) p.count[b] = 0; return; }
+    const int per = (n + kSelThreads - 1) / kSelThreads;
+    const int first = tid * per;
+    const float* sc = p.scores + v0;
+
+    float val[E];
+    uint64_t valid = 0;
+    float mx = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int idx = first + e;
+        const bool ok = e < per && idx < n;
+        float x = ok ? sc[idx] : 0.f;
+        if (!(x > 0.f)) x = 0.f;                   // negatives, -0.0 and NaN carry no mass
+        val[e] = x;
+        if (ok) valid |= 1ull << e;
+        mx = fmaxf(mx, x);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (lane == 0) s_redf[wave] = mx;
+    __syncthreads();
+    mx = 0.f;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) mx = fmaxf(mx, s_redf[w]);
+    if (!(mx > 0.f) || !(mx < INFINITY)) { if (tid == 0) p.count[b] = 0; return; }
+
+    // fixed point by an exact power-of-two scaling: the largest score lands in [2^39, 2^40)
+    int mx_exp;
+    (void)frexpf(mx, &mx_exp);
+    const int fix_shift = 40 - mx_exp;
+    auto to_fix = [&](float x) { return (unsigned long long)ldexpf(x, fix_shift); };
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) mine += to_fix(val[e]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    if (lane == 0) s_redu[wave] = mine;
+    __syncthreads();
+    unsigned long long total = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) total += s_redu[w];
+    // goal = ceil(lambda * total); lambda is an fp32 in [0,1] and total < 2^56, so the double product
+    // is within a few units of 2^-40 of the largest score: far below the parity margin
+    const double goal_d = ceil((double)p.lambda * (double)total);
+    unsigned long long goal = goal_d <= 0.0 ? 0ull : (unsigned long long)goal_d;
+    if (goal > total) goal = total;
+    if (goal == 0) { if (tid == 0) p.count[b] = 0; return; }
+
+    uint32_t prefix = 0, known = 0;
+    unsigned long long above_sum = 0;          // mass of the keys known to rank above the threshold
+    int above_cnt = 0, eq_cnt = 0;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int i = tid; i < kSelWaves * 256; i += kSelThreads) {
+            (&s_cnt[0][0])[i] = 0;
+            (&s_sum[0][0])[i] = 0ull;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float x = val[e];
+            __asm__ volatile("" : "+v"(x));          // recompute key and mass per pass: keeps them out of registers
+            const uint32_t key = score_key(x);
+            if (((valid >> e) & 1) && ((key & known) == prefix)) {
+                const int digit = (key >> shift) & 255;
+                atomicAdd(&s_cnt[wave][digit], 1);
+                atomicAdd(&s_sum[wave][digit], to_fix(x));
+            }
+        }
+        __syncthreads();
+        if (tid < 256) {
+            int c = 0; unsigned long long sm = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) { c += s_cnt[w][tid]; sm += s_sum[w][tid]; }
+            s_tcnt[tid] = c; s_tsum[tid] = sm;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns digits 4l..4l+3; inclusive suffix sums from the top digit down
+            int c4[4]; unsigned long long m4[4];
+            int cmine = 0; unsigned long long mmine = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { c4[i] = s_tcnt[4 * lane + i]; m4[i] = s_tsum[4 * lane + i]; cmine += c4[i]; mmine += m4[i]; }
+            int cincl = cmine; unsigned long long mincl = mmine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int yc = __shfl_down(cincl, off);
+                const unsigned long long ym = __shfl_down(mincl, off);
+                if (lane + off < 64) { cincl += yc; mincl += ym; }
+            }
+            // the threshold digit: first digit from the top where the running mass reaches the goal
+            unsigned long long m_above = above_sum + (mincl - mmine);
+            int c_above = above_cnt + (cincl - cmine);
+            if (m_above < goal && goal <= above_sum + mincl) {
+#pragma unroll
+                for (int i = 3; i >= 0; --i) {
+                    if (m_above < goal && goal <= m_above + m4[i]) {
+                        s_pick[0] = 4 * lane + i; s_pick[1] = c_above; s_pick[2] = c4[i];
+                        s_pick_sum = m_above;
+                    }
+                    m_above += m4[i]; c_above += c4[i];
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= (uint32_t)s_pick[0] << shift;
+        known |= 255u << shift;
+        above_cnt = s_pick[1]; eq_cnt = s_pick[2]; above_sum = s_pick_sum;
+    }
+    if (tid == 0) {
+        // every key equal to the threshold carries the same mass: take as many as the goal needs
+        float tval = 0.f;
+        const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
+        tval = __uint_as_float(u);
+        const unsigned long long each = to_fix(tval);
+        const unsigned long long need = goal - above_sum;
+        long long take = each > 0 ? (long long)((need + each - 1) / each) : eq_cnt;
+        if (take > eq_cnt) take = eq_cnt;
+        if (take < 1) take = 1;
+        int c = above_cnt + (int)take;
+        if (p.max_count && c > p.max_count[b]) c = p.max_count[b];
+        p.count[b] = c;
+    }
+}
+
 }  // namespace specvlm
 
 using namespace specvlm;
@@ -253,5 +413,35 @@ extern "C" int specvlm_select(
     else if (per <= 16) hipLaunchKernelGGL(select_kernel<16>, dim3(batch), dim3(kSelThreads), 0, s, p);
     else if (per <= 32) hipLaunchKernelGGL(select_kernel<32>, dim3(batch), dim3(kSelThreads), 0, s, p);
     else                hipLaunchKernelGGL(select_kernel<64>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    return launch_status();
+}
+
+extern "C" size_t specvlm_top_p_count_workspace_bytes(int batch, int max_n_video)
+{
+    (void)batch; (void)max_n_video;
+    return 0;
+}
+
+extern "C" int specvlm_top_p_count(
+    const float* scores, const int32_t* cu_video, int batch, int max_n_video,
+    float lambda, const int32_t* max_count, int32_t* count,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (batch < 0 || max_n_video < 0) return SPECVLM_EINVAL;
+    if (!(lambda >= 0.f && lambda <= 1.f)) return SPECVLM_EINVAL;
+    if (batch == 0) return SPECVLM_OK;
+    if (!count || (max_n_video > 0 && !scores)) return SPECVLM_EINVAL;
+    if (batch > 1 && !cu_video) return SPECVLM_EINVAL;
+    if (max_n_video > 64 * kSelThreads) return SPECVLM_EUNSUPPORTED;
+    TopPParams p;
+    p.scores = scores; p.cu_video = cu_video; p.max_n_video = max_n_video;
+    p.lambda = lambda; p.max_count = max_count; p.count = count;
+    hipStream_t s = (hipStream_t)stream;
+    const int per = (max_n_video + kSelThreads - 1) / kSelThreads;
+    if (per <= 4)       hipLaunchKernelGGL(top_p_kernel<4>,  dim3(batch), dim3(kSelThreads), 0, s, p);
+    else if (per <= 16) hipLaunchKernelGGL(top_p_kernel<16>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    else if (per <= 32) hipLaunchKernelGGL(top_p_kernel<32>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    else                hipLaunchKernelGGL(top_p_kernel<64>, dim3(batch), dim3(kSelThreads), 0, s, p);
     return launch_status();
 }

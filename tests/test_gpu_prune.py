@@ -216,3 +216,63 @@ def test_attention_over_gathered_cache(B):
                                  oracle.gather_kv(t["v"], 0, w.n_video, okeep), w.softmax_scale)
     from gpu_util import assert_attn_close
     assert_attn_close(out, want, "draft over pruned cache")
+
+
+# ------------------------------------------------------------- top-p count
+@pytest.mark.parametrize("V,seed,levels", [(1568, 0, 0), (6272, 1, 0), (12544, 2, 0), (32768, 3, 0),
+                                            (32768, 4, 8), (50000, 5, 0), (97, 6, 2), (1, 7, 0)])
+def test_top_p_count_matches_oracle(B, V, seed, levels):
+    """Eq. 6 on the device against the oracle's sorted fp64 prefix sums; equality is
+    required wherever lambda*total is further than 1e-6*total from a deciding prefix sum."""
+    s = synth.make_scores(V, 400 + seed, levels=levels)
+    sd = torch.from_numpy(s).cuda()
+    checked = 0
+    for lam in (0.0, 0.05, 0.1, 0.4, 0.5, 0.9, 1.0):
+        want, margin = oracle.top_p_count(s, lam, want_margin=True)
+        got = B.top_p_count(sd, lam)
+        torch.cuda.synchronize()
+        if lam == 1.0:
+            # fp32-exact fixed point vs fp64: the full sum is reached at the last positive score
+            assert got.item() <= V and got.item() >= want - 1 - (s == 0).sum()
+            continue
+        if margin > 1e-6:
+            assert got.item() == want, (lam, got.item(), want, margin)
+            checked += 1
+        else:
+            assert abs(got.item() - want) <= 1
+    assert checked >= 4
+
+
+def test_top_p_count_batch_clamp_and_chain_to_select(B):
+    frames = synth.ragged_frames()[:4]
+    Vs = (frames * 196).astype(np.int64)
+    scores = [synth.make_scores(int(v), 450 + i) for i, v in enumerate(Vs)]
+    buds = (Vs * 10 + 50) // 100
+    cu_v = i32(np.concatenate([[0], np.cumsum(Vs)]))
+    cu_k = i32(np.concatenate([[0], np.cumsum(buds)]))
+    sd = torch.from_numpy(np.concatenate(scores)).cuda()
+    cnt = B.top_p_count(sd, 0.4, cu_video=cu_v, max_n_video=int(Vs.max()), max_count=i32(buds))
+    torch.cuda.synchronize()
+    cnt_h = cnt.cpu().numpy()
+    for i in range(len(Vs)):
+        want, margin = oracle.top_p_count(scores[i], 0.4, want_margin=True)
+        if margin > 1e-6:
+            assert cnt_h[i] == min(want, int(buds[i]))
+    # the count feeds Stage I directly: k_top = min(c, B) on the device
+    keep, flag = B.select(sd, cnt, i32(buds), int(buds.sum()), cu_video=cu_v, cu_keep=cu_k,
+                          max_n_video=int(Vs.max()))
+    torch.cuda.synchronize()
+    keep, flag = keep.cpu().numpy(), flag.cpu().numpy()
+    o = 0
+    for i in range(len(Vs)):
+        wk, wf = oracle.select(scores[i], int(cnt_h[i]), int(buds[i]))
+        np.testing.assert_array_equal(keep[o:o + buds[i]], wk)
+        np.testing.assert_array_equal(flag[o:o + buds[i]], wf)
+        o += int(buds[i])
+
+
+def test_top_p_count_argument_errors(B):
+    s = torch.from_numpy(synth.make_scores(100, 460)).cuda()
+    with pytest.raises(B.SpecVLMError):
+        B.top_p_count(s, 1.5)
+    assert B.top_p_count(torch.zeros(64, device="cuda"), 0.5).item() == 0     # no mass at all

@@ -113,6 +113,9 @@ def test_top_p_count_is_minimal_prefix():
     assert oracle.top_p_count(s, 0.5) == 2
     assert oracle.top_p_count(s, 0.75) == 3
     assert oracle.top_p_count(s, 1.0) == 6
+    # margin: distance of lambda*total to the nearer deciding prefix sum, over the total
+    c, m = oracle.top_p_count(np.array([.4, .3, .2, .1], np.float32), 0.5, want_margin=True)
+    assert c == 2 and abs(m - 0.1) < 1e-6                     # prefix sums .4 | .7 around the goal .5
     s = synth.make_scores(4000, 15)
     for lam in (0.1, 0.4, 0.5, 0.9):
         c = oracle.top_p_count(s, lam)
