@@ -34,7 +34,7 @@ def lib():
         _lib = C.CDLL(build())
         for name in ("oracle_decode_attn", "oracle_score", "oracle_select", "oracle_top_p_count",
                      "oracle_gather_kv", "oracle_accept_greedy", "oracle_accept_sample",
-                     "oracle_final_token_interval"):
+                     "oracle_final_token_interval", "oracle_tree_attn", "oracle_accept_tree_greedy"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -158,3 +158,32 @@ def final_token_interval(target_logits, draft_logits, n: int, token: int, temper
     if rc:
         raise ValueError(f"oracle_final_token_interval rc={rc}")
     return lo.value, hi.value
+
+
+def tree_attn(q, k, v, mask, scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Block of tree nodes: node t sees the context and the block nodes whose bit is set in mask[t]."""
+    q, k, v = _u16(q), _u16(k), _u16(v)
+    mask = np.ascontiguousarray(mask, dtype=np.uint64)
+    q_len, hq, d = q.shape
+    kv_len, hkv, _ = k.shape
+    out = np.zeros((q_len, hq, d), dtype=np.float64)
+    lse = np.zeros((q_len, hq), dtype=np.float64)
+    rc = lib().oracle_tree_attn(_p(q), _p(k), _p(v), _p(mask), q_len, kv_len, hq, hkv, d,
+                                C.c_double(scale), _p(out), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_tree_attn rc={rc}")
+    return out, lse
+
+
+def accept_tree_greedy(target_logits, node_tokens, parent) -> Tuple[int, np.ndarray, np.ndarray]:
+    t = np.ascontiguousarray(target_logits, dtype=np.float32)
+    n_nodes, vocab = t.shape
+    x = np.ascontiguousarray(node_tokens, dtype=np.int32)
+    par = np.ascontiguousarray(parent, dtype=np.int32)
+    n = C.c_int32(0)
+    nodes = np.zeros(n_nodes, dtype=np.int32)
+    out = np.zeros(n_nodes, dtype=np.int32)
+    rc = lib().oracle_accept_tree_greedy(_p(t), _p(x), _p(par), n_nodes, vocab, C.byref(n), _p(nodes), _p(out))
+    if rc:
+        raise ValueError(f"oracle_accept_tree_greedy rc={rc}")
+    return int(n.value), nodes, out

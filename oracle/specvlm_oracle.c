@@ -411,3 +411,79 @@ int oracle_final_token_interval(const float* target_logits, const float* draft_l
     free(p); free(q);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Tree-masked verification  (Sec. 3.2 "Bonus": the draft tree is verified in
+ * one target forward through a specialised attention mask; App. B).
+ * The block's q_len tokens are tree nodes; node t sees every key before the
+ * block and, inside the block, node b iff bit b of mask[t] is set (its
+ * ancestors and itself).  A chain's mask, bits 0..t, gives oracle_decode_attn.
+ * ---------------------------------------------------------------------- */
+int oracle_tree_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint64_t* mask,
+                     int q_len, int kv_len, int n_q_heads, int n_kv_heads, int d,
+                     double scale, double* out, double* lse)
+{
+    if (q_len < 0 || q_len > 64 || kv_len < q_len || n_kv_heads < 1 || n_q_heads % n_kv_heads) return -1;
+    const int group = n_q_heads / n_kv_heads, ctx = kv_len - q_len;
+    const long rows = (long)q_len * n_q_heads;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < rows; ++r) {
+        const int t = (int)(r / n_q_heads), h = (int)(r % n_q_heads), g = h / group;
+        const uint16_t* qv = q + ((long)t * n_q_heads + h) * d;
+        double* s = (double*)malloc(sizeof(double) * (size_t)(kv_len > 0 ? kv_len : 1));
+        if (!s) { failed = 1; continue; }
+        double m = -INFINITY, z = 0.0;
+        for (int j = 0; j < kv_len; ++j) {
+            const int seen = j < ctx || ((mask[t] >> (j - ctx)) & 1);
+            s[j] = seen ? scale * dot_bf16(qv, k + ((long)j * n_kv_heads + g) * d, d) : -INFINITY;
+            if (s[j] > m) m = s[j];
+        }
+        for (int j = 0; j < kv_len; ++j) if (s[j] > -INFINITY) z += exp(s[j] - m);
+        double* o = out + r * d;
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        for (int j = 0; j < kv_len; ++j) {
+            if (!(s[j] > -INFINITY)) continue;
+            const double p = exp(s[j] - m) / z;
+            const uint16_t* vv = v + ((long)j * n_kv_heads + g) * d;
+            for (int c = 0; c < d; ++c) o[c] += p * bf16_to_f64(vv[c]);
+        }
+        if (lse) lse[r] = m + log(z);
+        free(s);
+    }
+    return failed ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Greedy acceptance over a draft tree  (App. B: verifying several candidates in
+ * one forward raises the accept length).  Node 0 is the last committed token;
+ * parent[i] < i for i >= 1.  Starting at node 0: the target's token at the
+ * current node is the argmax of its row (lowest index on ties); move to the
+ * lowest-numbered child that drafted exactly that token, if any.  The emitted
+ * tokens are the accepted nodes' tokens followed by the target's token at the
+ * node where the walk stops -- the target's own greedy continuation.
+ * ---------------------------------------------------------------------- */
+int oracle_accept_tree_greedy(const float* target_logits /* [n_nodes, vocab] */,
+                              const int32_t* node_tokens /* [n_nodes], entry 0 unused */,
+                              const int32_t* parent /* [n_nodes], parent[0] = -1 */,
+                              int n_nodes, int vocab, int32_t* n_accepted,
+                              int32_t* accepted_nodes /* [n_nodes] */, int32_t* out_tokens /* [n_nodes] */)
+{
+    if (n_nodes < 1 || vocab < 1) return -1;
+    for (int i = 1; i < n_nodes; ++i) if (parent[i] < 0 || parent[i] >= i) return -1;
+    for (int i = 0; i < n_nodes; ++i) { accepted_nodes[i] = -1; out_tokens[i] = -1; }
+    int cur = 0, n = 0;
+    for (;;) {
+        const int t = argmax_f32(target_logits + (long)cur * vocab, vocab);
+        int next = -1;
+        for (int c = cur + 1; c < n_nodes && next < 0; ++c)
+            if (parent[c] == cur && node_tokens[c] == t) next = c;
+        if (next < 0) { out_tokens[n] = t; break; }
+        accepted_nodes[n] = next;
+        out_tokens[n] = node_tokens[next];
+        ++n;
+        cur = next;
+    }
+    *n_accepted = n;
+    return 0;
+}

@@ -244,3 +244,33 @@ def make_accept_inputs(batch: int, gamma: int, vocab: int, seed: int, *,
     u = np.minimum(u, np.float32(1.0 - 2.0 ** -24)).astype(np.float32)
     return {"target_logits": target, "draft_logits": draft,
             "draft_tokens": tokens.reshape(batch, gamma), "uniforms": u}
+
+
+# --------------------------------------------------------------------------
+# Draft trees (structure only)
+# --------------------------------------------------------------------------
+def ancestor_masks(parent) -> np.ndarray:
+    """uint64 mask per node: bit b set iff b is the node itself or one of its ancestors."""
+    parent = np.asarray(parent, dtype=np.int64)
+    n = parent.shape[0]
+    masks = np.zeros(n, dtype=np.uint64)
+    for i in range(n):
+        m, j = 0, i
+        while j >= 0:
+            m |= 1 << int(j)
+            j = int(parent[j])
+        masks[i] = np.uint64(m)
+    return masks
+
+
+def make_tree(n_nodes: int, seed: int, max_children: int = 3) -> np.ndarray:
+    """A random static draft tree: parent[0] = -1, parent[i] < i, bounded fan-out."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    parent = np.full(n_nodes, -1, dtype=np.int32)
+    fan = np.zeros(n_nodes, dtype=np.int64)
+    for i in range(1, n_nodes):
+        cand = [j for j in range(i) if fan[j] < max_children]
+        j = int(rng.choice(cand))
+        parent[i] = j
+        fan[j] += 1
+    return parent
