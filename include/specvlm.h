@@ -10,6 +10,7 @@
  *   specvlm_gather_kv    the draft's pruned KV cache           (Sec. 3.2, last paragraph)
  *   specvlm_decode_attn  draft decode / parallel verification  (Sec. 2.1)
  *   specvlm_accept       draft-token acceptance                (Sec. 2.1; App. A greedy)
+ *   specvlm_tree_attn / specvlm_accept_tree   the same two steps for a draft tree (App. B)
  *
  * Conventions shared by every call
  * --------------------------------
@@ -208,6 +209,26 @@ int specvlm_decode_attn(
     void* workspace, size_t workspace_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * specvlm_tree_attn -- specvlm_decode_attn for a block of draft-TREE nodes
+ * (Sec. 3.2 "Bonus" and App. B: the tree is verified in one target forward
+ * through a specialised attention mask).  Same arguments as specvlm_decode_attn
+ * plus
+ *   ancestor_mask  device uint64 [sum q_len_b]: query t of a request sees every
+ *                  key before its block and block key b iff bit b of its mask
+ *                  is set (node b is t itself or one of its ancestors).  Every
+ *                  row must have its own bit set.  q_len <= 64.
+ * The chain mask (bits 0..t for query t) reproduces specvlm_decode_attn.
+ * Workspace: specvlm_decode_attn_workspace_bytes of the same shape.
+ * -------------------------------------------------------------------------- */
+int specvlm_tree_attn(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    const uint64_t* ancestor_mask, void* out, float* lse, int num_splits,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
  * specvlm_accept -- which drafted tokens survive verification  (Sec. 2.1).
  *
  * Greedy (uniforms == NULL, then draft_logits must be NULL too; App. A: the target decodes
@@ -233,6 +254,28 @@ int specvlm_accept(
     const int32_t* draft_tokens, const float* uniforms,
     int batch, int gamma, int vocab, float temperature,
     int32_t* n_accepted, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * specvlm_accept_tree -- greedy acceptance over a static draft tree (App. B).
+ * Row i of target_logits is the target's next-token distribution at tree node
+ * i; node 0 is the last committed token, parent[i] < i for i >= 1 (one tree
+ * shared by the batch).  Starting at node 0: t = argmax of the current node's
+ * row (lowest index on ties); move to the lowest-numbered child whose drafted
+ * token equals t; stop when there is none.
+ *   target_logits fp32 [batch, n_nodes, vocab]   node_tokens int32 [batch, n_nodes] (entry 0 unused)
+ *   parent int32 [n_nodes] (device)              n_accepted int32 [batch]
+ *   accepted_nodes int32 [batch, n_nodes]: the accepted path, then -1
+ *   out_tokens int32 [batch, n_nodes]: the accepted tokens, the target's token at
+ *               the stopping node, then -1 (the target's own greedy continuation)
+ * n_nodes <= 64.
+ * -------------------------------------------------------------------------- */
+size_t specvlm_accept_tree_workspace_bytes(int batch, int n_nodes, int vocab);
+
+int specvlm_accept_tree(
+    const float* target_logits, const int32_t* node_tokens, const int32_t* parent,
+    int batch, int n_nodes, int vocab,
+    int32_t* n_accepted, int32_t* accepted_nodes, int32_t* out_tokens,
     void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus

@@ -25,6 +25,7 @@ EXPORTS = (
     "specvlm_gather_kv",
     "specvlm_decode_attn_workspace_bytes", "specvlm_decode_attn",
     "specvlm_accept_workspace_bytes", "specvlm_accept",
+    "specvlm_tree_attn", "specvlm_accept_tree_workspace_bytes", "specvlm_accept_tree",
 )
 
 
@@ -63,10 +64,14 @@ def lib() -> C.CDLL:
         l.specvlm_decode_attn_workspace_bytes.argtypes = [i32] * 7
         l.specvlm_decode_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
                                           i32, i32, i32, f32, vp, vp, i32, vp, sz, vp]
+        l.specvlm_tree_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
+                                        i32, i32, i32, f32, vp, vp, vp, i32, vp, sz, vp]
+        l.specvlm_accept_tree_workspace_bytes.argtypes = [i32] * 3
+        l.specvlm_accept_tree.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
         for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
-                     "specvlm_decode_attn", "specvlm_accept"):
+                     "specvlm_decode_attn", "specvlm_accept", "specvlm_tree_attn", "specvlm_accept_tree"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -223,7 +228,7 @@ def decode_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale
                 cu_q: Optional[torch.Tensor] = None, cu_kv: Optional[torch.Tensor] = None,
                 max_q_len: Optional[int] = None, max_kv_len: Optional[int] = None,
                 out: Optional[torch.Tensor] = None, want_lse: bool = False, num_splits: int = 0,
-                workspace: Optional[torch.Tensor] = None):
+                workspace: Optional[torch.Tensor] = None, ancestor_mask: Optional[torch.Tensor] = None):
     """q [sum q_len,H_q,d], k/v [sum kv_len,H_kv,d] bf16 views -> out like q (and lse fp32)."""
     tq, hq, d = q.shape
     tk, hkv, _ = k.shape
@@ -244,12 +249,24 @@ def decode_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale
     need = decode_attn_workspace_bytes(batch, q_len, kv_len, hq, hkv, d, num_splits)
     workspace = _ws(workspace, need, q)
     qs, ks = _thd(q), _thd(k)
-    rc = lib().specvlm_decode_attn(_ptr(q), qs[0], qs[1], _ptr(k), _ptr(v), ks[0], ks[1],
-                                   _ptr(cu_q), _ptr(cu_kv), batch, q_len, kv_len, hq, hkv, d,
-                                   float(softmax_scale), _ptr(out), _ptr(lse), num_splits,
-                                   _ptr(workspace), workspace.numel(), _stream())
-    _check("specvlm_decode_attn", rc)
+    if ancestor_mask is None:
+        rc = lib().specvlm_decode_attn(_ptr(q), qs[0], qs[1], _ptr(k), _ptr(v), ks[0], ks[1],
+                                       _ptr(cu_q), _ptr(cu_kv), batch, q_len, kv_len, hq, hkv, d,
+                                       float(softmax_scale), _ptr(out), _ptr(lse), num_splits,
+                                       _ptr(workspace), workspace.numel(), _stream())
+        _check("specvlm_decode_attn", rc)
+    else:
+        rc = lib().specvlm_tree_attn(_ptr(q), qs[0], qs[1], _ptr(k), _ptr(v), ks[0], ks[1],
+                                     _ptr(cu_q), _ptr(cu_kv), batch, q_len, kv_len, hq, hkv, d,
+                                     float(softmax_scale), _ptr(ancestor_mask), _ptr(out), _ptr(lse),
+                                     num_splits, _ptr(workspace), workspace.numel(), _stream())
+        _check("specvlm_tree_attn", rc)
     return (out, lse) if want_lse else out
+
+
+def tree_attn(q, k, v, softmax_scale, ancestor_mask: torch.Tensor, **kw):
+    """decode_attn for a block of draft-tree nodes; ancestor_mask int64/uint64 [sum q_len]."""
+    return decode_attn(q, k, v, softmax_scale, ancestor_mask=ancestor_mask, **kw)
 
 
 # -------------------------------------------------------------------------- accept
@@ -279,3 +296,24 @@ def accept(target_logits: torch.Tensor, draft_tokens: torch.Tensor, *,
                               _ptr(n_acc), _ptr(out), _ptr(workspace), workspace.numel(), _stream())
     _check("specvlm_accept", rc)
     return n_acc, out
+
+
+def accept_tree(target_logits: torch.Tensor, node_tokens: torch.Tensor, parent: torch.Tensor, *,
+                workspace: Optional[torch.Tensor] = None):
+    """target_logits fp32 [batch, n_nodes, vocab], node_tokens int32 [batch, n_nodes], parent int32 [n_nodes]
+    -> (n_accepted [batch], accepted_nodes [batch, n_nodes], out_tokens [batch, n_nodes])."""
+    batch, n_nodes, vocab = target_logits.shape
+    dev = target_logits.device
+    n_acc = torch.empty(batch, dtype=torch.int32, device=dev)
+    nodes = torch.empty((batch, n_nodes), dtype=torch.int32, device=dev)
+    out = torch.empty((batch, n_nodes), dtype=torch.int32, device=dev)
+    need = lib().specvlm_accept_tree_workspace_bytes(batch, n_nodes, vocab)
+    workspace = _ws(workspace, need, target_logits)
+    for t in (target_logits, node_tokens, parent):
+        if not t.is_contiguous():
+            raise ValueError("accept_tree inputs must be contiguous")
+    rc = lib().specvlm_accept_tree(_ptr(target_logits), _ptr(node_tokens), _ptr(parent), batch, n_nodes,
+                                   vocab, _ptr(n_acc), _ptr(nodes), _ptr(out), _ptr(workspace),
+                                   workspace.numel(), _stream())
+    _check("specvlm_accept_tree", rc)
+    return n_acc, nodes, out

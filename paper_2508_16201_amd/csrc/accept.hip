@@ -239,6 +239,45 @@ void accept_sample_final(const AcceptParams p)
     }
 }
 
+// ------------------------------------------------------------------ tree ----
+// Greedy walk over a static draft tree (App. B): rows of target_logits are tree
+// nodes; node 0 is the last committed token, parent[i] < i.  One wave per
+// request merges the per-chunk argmax partials of every node, then lane 0
+// walks from the root, moving to the lowest-numbered child that drafted the
+// target's token.
+__global__ __launch_bounds__(64)
+void accept_tree_final(const AcceptParams p, const int32_t* parent, int32_t* accepted_nodes)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int n_nodes = p.gamma + 1;
+    __shared__ int s_t[65];
+    for (int row = lane; row < n_nodes; row += 64) {
+        float bv = 0.f; int bi = -1;
+        const int64_t slot = ((int64_t)b * n_nodes + row) * p.n_chunks;
+        for (int c = 0; c < p.n_chunks; ++c)
+            argmax_merge(bv, bi, p.part_val[slot + c], __float_as_int(p.part_aux[slot + c]));
+        s_t[row] = bi;
+    }
+    __syncthreads();
+    if (lane != 0) return;
+    const int32_t* x = p.tokens + (int64_t)b * n_nodes;
+    int32_t* out = p.out_tokens + (int64_t)b * n_nodes;
+    int32_t* nodes = accepted_nodes + (int64_t)b * n_nodes;
+    int cur = 0, n = 0;
+    for (;;) {
+        const int t = s_t[cur];
+        int next = -1;
+        for (int c = cur + 1; c < n_nodes && next < 0; ++c)
+            if (parent[c] == cur && x[c] == t) next = c;
+        if (next < 0) { out[n] = t; break; }
+        nodes[n] = next; out[n] = x[next];
+        ++n; cur = next;
+    }
+    for (int i = n; i < n_nodes; ++i) nodes[i] = -1;
+    for (int i = n + 1; i < n_nodes; ++i) out[i] = -1;
+    p.n_accepted[b] = n;
+}
+
 static int accept_chunks(int vocab) { return (vocab + kAccChunk - 1) / kAccChunk; }
 
 }  // namespace specvlm
@@ -286,5 +325,37 @@ extern "C" int specvlm_accept(
         hipLaunchKernelGGL(accept_softmax_partial, dim3(p.n_chunks, 2 * gamma + 1, batch), dim3(256), 0, s, p);
         hipLaunchKernelGGL(accept_sample_final, dim3(batch), dim3(kAccThreads), 0, s, p);
     }
+    return launch_status();
+}
+
+extern "C" size_t specvlm_accept_tree_workspace_bytes(int batch, int n_nodes, int vocab)
+{
+    return specvlm_accept_workspace_bytes(batch, n_nodes - 1, vocab, 0);
+}
+
+extern "C" int specvlm_accept_tree(
+    const float* target_logits, const int32_t* node_tokens, const int32_t* parent,
+    int batch, int n_nodes, int vocab,
+    int32_t* n_accepted, int32_t* accepted_nodes, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch < 0 || n_nodes < 1 || vocab < 1) return SPECVLM_EINVAL;
+    if (n_nodes > 64) return SPECVLM_EUNSUPPORTED;
+    if (batch == 0) return SPECVLM_OK;
+    if (!target_logits || !node_tokens || !parent || !n_accepted || !accepted_nodes || !out_tokens)
+        return SPECVLM_EINVAL;
+    if (batch > 65535) return SPECVLM_EUNSUPPORTED;
+    const size_t need = specvlm_accept_tree_workspace_bytes(batch, n_nodes, vocab);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) return SPECVLM_EWORKSPACE;
+    AcceptParams p;
+    p.target = target_logits; p.draft = nullptr; p.tokens = node_tokens; p.uniforms = nullptr;
+    p.batch = batch; p.gamma = n_nodes - 1; p.vocab = vocab; p.n_chunks = accept_chunks(vocab);
+    p.inv_t_log2 = kLog2e;
+    p.n_accepted = n_accepted; p.out_tokens = out_tokens;
+    p.part_val = (float*)workspace;
+    p.part_aux = (float*)((char*)workspace + need / 2);
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(accept_argmax_partial, dim3(p.n_chunks, n_nodes, batch), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(accept_tree_final, dim3(batch), dim3(64), 0, s, p, parent, accepted_nodes);
     return launch_status();
 }

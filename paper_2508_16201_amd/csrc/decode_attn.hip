@@ -55,6 +55,7 @@ struct AttnParams {
     int rows_pad;
     int n_work;
     int heads_fastest;
+    const uint64_t* block_mask;  // [sum q_len] tree masks of the block's queries, or null (chain)
 };
 
 constexpr int kChunkKeys = 32;       // keys per PV contraction step
@@ -171,13 +172,14 @@ void attn_split_kernel(const AttnParams p)
 
     // ---- this wave's Q fragments (B operand of S^T) and the row's last visible key ----
     bf16x8 qf[KK];
-    int last_key;
+    uint64_t row_mask;          // which of the block's own keys this query row sees (bit b = block key b)
     {
         const int row = mb * 16 + r;
         const bool live = row < n_rows;
         const int t = live ? row / p.group : 0;
         const int h = g * p.group + (live ? row % p.group : 0);
-        last_key = kvl - ql + t;
+        // chain: the block is causal, query t sees block keys 0..t; tree: the caller's ancestor mask
+        row_mask = p.block_mask ? p.block_mask[q0 + t] : ((2ull << t) - 1ull);
         const __bf16* qp = p.q + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + c * 8;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
@@ -229,7 +231,7 @@ void attn_split_kernel(const AttnParams p)
             const int chunk = ks + cc * KS;
             const int base = k_begin + tile * TK + chunk * kChunkKeys;
             if (base >= k_end) break;
-            const bool need_mask = (base + kChunkKeys > k_end) || (base + kChunkKeys - 1 > kvl - ql);
+            const bool need_mask = (base + kChunkKeys > k_end) || (base + kChunkKeys > kvl - ql);
             // ---- S^T = K Q^T for 32 keys ----
             floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -254,10 +256,14 @@ void attn_split_kernel(const AttnParams p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) { s[i] = s0[i] * p.scale_log2; s[4 + i] = s1[i] * p.scale_log2; }
             if (need_mask) {
+                const uint32_t mask_lo = (uint32_t)row_mask, mask_hi = (uint32_t)(row_mask >> 32);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int key = base + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
-                    if (key >= k_end || key > last_key) s[i] = -INFINITY;
+                    const int bk = key - (kvl - ql);        // index inside the block (negative: context key)
+                    const uint32_t word = (bk & 32) ? mask_hi : mask_lo;
+                    const bool in_block_hidden = bk >= 0 && ((word >> (bk & 31)) & 1u) == 0u;
+                    s[i] = (key >= k_end || in_block_hidden) ? -INFINITY : s[i];
                 }
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
@@ -563,12 +569,12 @@ extern "C" size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int 
     return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float));
 }
 
-extern "C" int specvlm_decode_attn(
+static int attn_impl(
     const void* q, int64_t q_tok_stride, int64_t q_head_stride,
     const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
     const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
     int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
-    void* out, float* lse, int num_splits,
+    const uint64_t* block_mask, void* out, float* lse, int num_splits,
     void* workspace, size_t workspace_bytes, void* stream)
 {
     if (batch < 0 || q_len < 0 || kv_len < 0 || n_q_heads <= 0 || n_kv_heads <= 0) return SPECVLM_EINVAL;
@@ -596,7 +602,7 @@ extern "C" int specvlm_decode_attn(
     p.out = (__bf16*)out; p.lse = lse;
     p.q_tok = q_tok_stride; p.q_head = q_head_stride;
     p.kv_tok = kv_tok_stride; p.kv_head = kv_head_stride;
-    p.cu_q = cu_q; p.cu_kv = cu_kv;
+    p.cu_q = cu_q; p.cu_kv = cu_kv; p.block_mask = block_mask;
     p.batch = batch; p.q_len = q_len; p.kv_len = kv_len;
     p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = group;
     p.scale_log2 = softmax_scale * kLog2e;
@@ -624,4 +630,32 @@ extern "C" int specvlm_decode_attn(
         rc = launch_status();
     }
     return rc;
+}
+
+extern "C" int specvlm_decode_attn(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    void* out, float* lse, int num_splits,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attn_impl(q, q_tok_stride, q_head_stride, k, v, kv_tok_stride, kv_head_stride, cu_q, cu_kv,
+                     batch, q_len, kv_len, n_q_heads, n_kv_heads, head_dim, softmax_scale, nullptr,
+                     out, lse, num_splits, workspace, workspace_bytes, stream);
+}
+
+extern "C" int specvlm_tree_attn(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    const uint64_t* ancestor_mask, void* out, float* lse, int num_splits,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ancestor_mask && batch > 0 && q_len > 0) return SPECVLM_EINVAL;
+    if (q_len > 64) return SPECVLM_EUNSUPPORTED;
+    return attn_impl(q, q_tok_stride, q_head_stride, k, v, kv_tok_stride, kv_head_stride, cu_q, cu_kv,
+                     batch, q_len, kv_len, n_q_heads, n_kv_heads, head_dim, softmax_scale, ancestor_mask,
+                     out, lse, num_splits, workspace, workspace_bytes, stream);
 }
