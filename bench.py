@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sampling", action="store_true", help="rejection-sampling accept instead of greedy")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying HIP graphs")
+    ap.add_argument("--score-lse", action="store_true",
+                    help="hand the score call each row's softmax normaliser (as a prefill attention would "
+                         "have saved it), so scoring is one sweep per layer")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count (with --attn-only)")
     ap.add_argument("--attn-only", action="store_true",
                     help="time only the verify attention of --workload (32b-long, ragged-x8, ...): extra context "
@@ -144,10 +147,24 @@ def main():
     n_acc = torch.zeros(1, dtype=torch.int32, device=dev)
     out_tok = torch.zeros((1, g1), dtype=torch.int32, device=dev)
 
+    # Row normalisers of the text queries, as the verifier's prefill attention would have saved them
+    # (set-up only: plain torch, outside the timed region).
+    row_lse = None
+    if args.score_lse:
+        row_lse = torch.empty((L, T, hq), dtype=torch.float32, device=dev)
+        hidden = torch.arange(n_ctx, device=dev)[None, :] > (V + torch.arange(T, device=dev))[:, None]
+        for l in range(L):
+            qf = q_text[l].float().permute(1, 0, 2)                                       # [hq, T, d]
+            kf = k_all[l, :n_ctx].float().permute(1, 0, 2).repeat_interleave(hq // hkv, dim=0)
+            logits = torch.bmm(qf, kf.transpose(1, 2)) * scale                           # [hq, T, n_ctx]
+            logits.masked_fill_(hidden[None], float("-inf"))
+            row_lse[l] = torch.logsumexp(logits, dim=-1).transpose(0, 1)
+        del qf, kf, logits
+
     def st_score():
         for l in range(L):
             B.score(q_text[l], k_all[l, :n_ctx], 0, V, V, scale, beta=(1.0 if l else 0.0),
-                    scores=scores, workspace=ws_score)
+                    row_lse=None if row_lse is None else row_lse[l], scores=scores, workspace=ws_score)
 
     def st_select():
         B.select(scores, k_top_d, budget_d, budget, want_flags=False, keep_idx=keep)
@@ -248,6 +265,7 @@ def main():
                                f"draft {dq}/{dkv} d{dd} x{dl} layers",
                    "kv_layout": args.layout, "num_splits": args.num_splits,
                    "accept": "sampling" if args.sampling else "greedy",
+                   "score_row_lse": "supplied" if args.score_lse else "computed",
                    "launch": "eager" if args.eager else "hip-graph per stage"},
         "pct_of_hbm_peak": round(100.0 * attn_gbs2 / HBM_PEAK_GBS, 1),
         "prune_gather_us": round((stage_ms["select"] + stage_ms["gather"]) * 1e3, 1),
@@ -261,6 +279,7 @@ def main():
         "draft_attn_us_per_layer": round(stage_ms["draft_attn"] * 1e3 / (w.gamma * dl), 3),
         "gather_gbs": round(gather_bytes / (stage_ms["gather"] * 1e-3) / 1e9, 1),
         "n_accepted": int(n_acc.item()),
+        "score_mass_on_video": round(float(scores.sum().item()), 4),
         "roofline": {"kernel": "specvlm_decode_attn (verify, split + merge)", "bound": "hbm",
                      "achieved": round(attn_gbs2, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(attn_gbs2 / HBM_PEAK_GBS, 4),

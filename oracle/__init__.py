@@ -187,3 +187,27 @@ def accept_tree_greedy(target_logits, node_tokens, parent) -> Tuple[int, np.ndar
     if rc:
         raise ValueError(f"oracle_accept_tree_greedy rc={rc}")
     return int(n.value), nodes, out
+
+
+BASELINE_MODES = {"window-front": 0, "window-middle": 1, "window-end": 2, "uniform": 3,
+                  "frame-drop": 4, "lattice": 5, "random": 6}
+
+
+def splitmix64(seed: int, j: int) -> int:
+    fn = lib().oracle_splitmix64
+    fn.restype = C.c_uint64
+    fn.argtypes = [C.c_uint64, C.c_uint64]
+    return int(fn(seed, j))
+
+
+def baseline_keep(mode: str, n_video: int, keep_budget: int, *, n_frames: int = 0, grid_h: int = 0,
+                  grid_w: int = 0, stride_h: int = 1, stride_w: int = 1, seed: int = 0) -> np.ndarray:
+    """Attention-agnostic retention set of the named ablation pruner -> ascending int32 indices."""
+    buf = np.zeros(max(n_video, 1), dtype=np.int32)
+    fn = lib().oracle_baseline_keep
+    fn.argtypes = [C.c_int] * 8 + [C.c_uint64, C.c_void_p]
+    n = fn(BASELINE_MODES[mode], n_video, n_frames, grid_h, grid_w, keep_budget, stride_h, stride_w,
+           seed, _p(buf))
+    if n < 0:
+        raise ValueError(f"oracle_baseline_keep rc={n}")
+    return buf[:n].copy()

@@ -487,3 +487,94 @@ int oracle_accept_tree_greedy(const float* target_logits /* [n_nodes, vocab] */,
     *n_accepted = n;
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Attention-agnostic retention sets the paper compares against (Sec. 5.2 ablation
+ * and "Exploration of Diverse Pruning Criteria"; the random pruning of Sec. 2.2).
+ * Video tokens are numbered frame-major, then row-major on the frame's
+ * grid_h x grid_w grid.  Every mode writes ascending indices and returns how
+ * many it wrote (negative: invalid arguments).
+ *   0 window, front  : tokens 0 .. B-1
+ *   1 window, middle : B consecutive tokens starting at floor((V-B)/2)
+ *   2 window, end    : tokens V-B .. V-1
+ *   3 uniform, flat  : tokens floor(t*V/B), t = 0..B-1 (Stage II alone, nothing taken by Stage I)
+ *   4 frame dropping : F_k = floor(B / tokens per frame) whole frames at the regular
+ *                      temporal interval F/F_k: frames floor(t*F/F_k)
+ *   5 spatial lattice: in every frame the grid positions whose row is a multiple of
+ *                      stride_h and whose column is a multiple of stride_w (B unused)
+ *   6 random         : token j draws the 30 high bits of the j-th output of the
+ *                      SplitMix64 generator seeded with `seed`; the B largest draws
+ *                      are kept (equal draws: lower index first)
+ * ---------------------------------------------------------------------- */
+uint64_t oracle_splitmix64(uint64_t seed, uint64_t j)   /* j-th output (j = 0 first) of the stream */
+{
+    uint64_t z = seed + (j + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+typedef struct { uint32_t draw; int32_t idx; } drawn_t;
+
+static int cmp_draw_desc(const void* pa, const void* pb)
+{
+    const drawn_t* a = (const drawn_t*)pa;
+    const drawn_t* b = (const drawn_t*)pb;
+    if (a->draw != b->draw) return a->draw > b->draw ? -1 : 1;
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+static int cmp_i32(const void* pa, const void* pb)
+{
+    const int32_t a = *(const int32_t*)pa, b = *(const int32_t*)pb;
+    return (a > b) - (a < b);
+}
+
+int oracle_baseline_keep(int mode, int n_video, int n_frames, int grid_h, int grid_w,
+                         int keep_budget, int stride_h, int stride_w, uint64_t seed,
+                         int32_t* keep_idx)
+{
+    const int64_t V = n_video, B = keep_budget;
+    if (V < 0 || B < 0 || B > V) return -1;
+    const int64_t tpf = (int64_t)grid_h * grid_w;
+    if (mode == 4 || mode == 5) {
+        if (n_frames < 0 || grid_h <= 0 || grid_w <= 0 || tpf * n_frames != V) return -1;
+    }
+    int n = 0;
+    switch (mode) {
+    case 0: for (int64_t t = 0; t < B; ++t) keep_idx[n++] = (int32_t)t; break;
+    case 1: for (int64_t t = 0; t < B; ++t) keep_idx[n++] = (int32_t)((V - B) / 2 + t); break;
+    case 2: for (int64_t t = 0; t < B; ++t) keep_idx[n++] = (int32_t)(V - B + t); break;
+    case 3: for (int64_t t = 0; t < B; ++t) keep_idx[n++] = (int32_t)((t * V) / B); break;
+    case 4: {
+        const int64_t fk = B / tpf;
+        for (int64_t t = 0; t < fk; ++t) {
+            const int64_t f = (t * n_frames) / fk;
+            for (int64_t w = 0; w < tpf; ++w) keep_idx[n++] = (int32_t)(f * tpf + w);
+        }
+        break;
+    }
+    case 5:
+        if (stride_h <= 0 || stride_w <= 0) return -1;
+        for (int f = 0; f < n_frames; ++f)
+            for (int r = 0; r < grid_h; r += stride_h)
+                for (int c = 0; c < grid_w; c += stride_w)
+                    keep_idx[n++] = (int32_t)(f * tpf + (int64_t)r * grid_w + c);
+        break;
+    case 6: {
+        drawn_t* order = (drawn_t*)malloc(sizeof(drawn_t) * (size_t)(V > 0 ? V : 1));
+        if (!order) return -2;
+        for (int64_t j = 0; j < V; ++j) {
+            order[j].draw = (uint32_t)(oracle_splitmix64(seed, (uint64_t)j) >> 34);
+            order[j].idx = (int32_t)j;
+        }
+        qsort(order, (size_t)V, sizeof(drawn_t), cmp_draw_desc);
+        for (int64_t t = 0; t < B; ++t) keep_idx[n++] = order[t].idx;
+        qsort(keep_idx, (size_t)n, sizeof(int32_t), cmp_i32);
+        free(order);
+        break;
+    }
+    default: return -1;
+    }
+    return n;
+}

@@ -126,9 +126,14 @@ V32B_LONG = Workload("32b-long", 128, 16, 16, 256, 40, 8, 128, n_layers=64, gamm
 RAGGED = Workload("ragged-x8", 0, 14, 14, 256, 64, 8, 128, n_layers=1, gamma=5,
                   vocab=152064, draft_q_heads=28, draft_kv_heads=4, draft_head_dim=128,
                   draft_layers=1, index=4)
+# Self-speculation with the 7B model (Sec. 4.1: 128 frames of 196 tokens): the draft is the verifier's
+# own weights over the pruned cache, so both caches have the 28/4-head, 28-layer shape.
+V7B_SELF = Workload("7b-self", 128, 14, 14, 256, 28, 4, 128, n_layers=28, gamma=5,
+                    vocab=152064, draft_q_heads=28, draft_kv_heads=4, draft_head_dim=128,
+                    draft_layers=28, index=5)
 
 WORKLOADS: Dict[str, Workload] = {w.name: w for w in
-                                  (TINY, V72B_1L, V72B_FULL, V32B_LONG, RAGGED)}
+                                  (TINY, V72B_1L, V72B_FULL, V32B_LONG, RAGGED, V7B_SELF)}
 
 
 def scaled(w: Workload, **kw) -> Workload:

@@ -50,6 +50,8 @@ def run_case(B, q_len, kv_len, hq, hkv, d, seed, num_splits=0, scale=None, head_
     (6, 1000, 16, 2, 128, 1),
     (8, 2077, 10, 2, 128, 3),      # group 5 (32B-shaped), gamma 7
     (8, 777, 16, 2, 128, 2),       # 64 rows: 4 row blocks
+    (6, 2900, 28, 4, 128, 0),      # 7B-shaped heads (group 7): 42 rows, 3 row blocks with a ragged last one
+    (1, 2900, 28, 4, 128, 0),
     (4, 515, 40, 8, 128, 0),
     (6, 6, 8, 1, 128, 0),          # cache holds only the block itself
     (3, 130, 2, 2, 64, 0),         # group 1

@@ -42,6 +42,8 @@ def assert_scores_close(got, want, what=""):
     (700, 37, 5, 16, 2, 128, 1),
     (1000, 130, 0, 10, 2, 128, 0),    # group 5
     (333, 3, 0, 8, 8, 64, 0),         # group 1, fewer rows than one tile
+    (1176, 70, 0, 28, 4, 128, 0),     # 7B-shaped heads (group 7): 6 frames of 196
+    (1176, 70, 0, 28, 4, 128, 1),
 ])
 def test_score_matches_oracle(B, V, L, P, hq, hkv, d, mode):
     n_keys = P + V + L
