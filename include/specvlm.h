@@ -278,6 +278,46 @@ int specvlm_accept_tree(
     int32_t* n_accepted, int32_t* accepted_nodes, int32_t* out_tokens,
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* --------------------------------------------------------------------------
+ * specvlm_baseline_keep -- retention sets of the attention-agnostic pruners the
+ * ablations compare with (Sec. 2.2 random pruning; Sec. 5.2: windows over the
+ * front / middle / end of the video, SD-Uniform, SD-Frame).  One request.
+ * Video tokens are numbered frame-major, then row-major on the frame's
+ * grid_h x grid_w grid; V = n_video, B = keep_budget (0 <= B <= V).
+ *   WINDOW_FRONT   tokens 0..B-1
+ *   WINDOW_MIDDLE  B consecutive tokens from floor((V-B)/2)
+ *   WINDOW_END     tokens V-B..V-1
+ *   UNIFORM        tokens floor(t*V/B), t = 0..B-1 (Eq. 7 with an empty V_R)
+ *   FRAME_DROP     F_k = floor(B / (grid_h*grid_w)) whole frames, frames floor(t*F/F_k)
+ *   LATTICE        in every frame the rows that are multiples of stride_h and the
+ *                  columns that are multiples of stride_w (B unused)
+ *   RANDOM         token j draws the 30 high bits of output j of the SplitMix64
+ *                  stream seeded with `seed`; the B largest draws are kept, equal
+ *                  draws by lower index (V <= 65536)
+ * FRAME_DROP and LATTICE need n_frames*grid_h*grid_w == V; the other modes
+ * ignore the grid arguments.  specvlm_baseline_count (host arithmetic only)
+ * returns how many indices the mode writes, or a negative status;
+ * keep_idx (device int32, that many entries) receives them in ascending order.
+ * Only RANDOM needs a workspace.
+ * -------------------------------------------------------------------------- */
+#define SPECVLM_BASELINE_WINDOW_FRONT  0
+#define SPECVLM_BASELINE_WINDOW_MIDDLE 1
+#define SPECVLM_BASELINE_WINDOW_END    2
+#define SPECVLM_BASELINE_UNIFORM       3
+#define SPECVLM_BASELINE_FRAME_DROP    4
+#define SPECVLM_BASELINE_LATTICE       5
+#define SPECVLM_BASELINE_RANDOM        6
+
+int specvlm_baseline_count(int mode, int n_video, int n_frames, int grid_h, int grid_w,
+                           int keep_budget, int stride_h, int stride_w);
+
+size_t specvlm_baseline_workspace_bytes(int mode, int n_video);
+
+int specvlm_baseline_keep(
+    int mode, int n_video, int n_frames, int grid_h, int grid_w,
+    int keep_budget, int stride_h, int stride_w, uint64_t seed,
+    int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

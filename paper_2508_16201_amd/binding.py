@@ -26,6 +26,7 @@ EXPORTS = (
     "specvlm_decode_attn_workspace_bytes", "specvlm_decode_attn",
     "specvlm_accept_workspace_bytes", "specvlm_accept",
     "specvlm_tree_attn", "specvlm_accept_tree_workspace_bytes", "specvlm_accept_tree",
+    "specvlm_baseline_count", "specvlm_baseline_workspace_bytes", "specvlm_baseline_keep",
 )
 
 
@@ -68,6 +69,11 @@ def lib() -> C.CDLL:
                                         i32, i32, i32, f32, vp, vp, vp, i32, vp, sz, vp]
         l.specvlm_accept_tree_workspace_bytes.argtypes = [i32] * 3
         l.specvlm_accept_tree.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        l.specvlm_baseline_count.argtypes = [i32] * 8
+        l.specvlm_baseline_count.restype = C.c_int
+        l.specvlm_baseline_workspace_bytes.argtypes = [i32] * 2
+        l.specvlm_baseline_keep.argtypes = [i32] * 8 + [C.c_uint64, vp, vp, sz, vp]
+        l.specvlm_baseline_keep.restype = C.c_int
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
         for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
@@ -317,3 +323,27 @@ def accept_tree(target_logits: torch.Tensor, node_tokens: torch.Tensor, parent: 
                                    workspace.numel(), _stream())
     _check("specvlm_accept_tree", rc)
     return n_acc, nodes, out
+
+
+# ------------------------------------------------------------------- baseline pruners
+BASELINE_MODES = {"window-front": 0, "window-middle": 1, "window-end": 2, "uniform": 3,
+                  "frame-drop": 4, "lattice": 5, "random": 6}
+
+
+def baseline_keep(mode: str, n_video: int, keep_budget: int, *, n_frames: int = 0, grid_h: int = 0,
+                  grid_w: int = 0, stride_h: int = 1, stride_w: int = 1, seed: int = 0,
+                  device=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Retention set of the named attention-agnostic pruner -> ascending int32 indices on the device."""
+    m = BASELINE_MODES[mode]
+    count = lib().specvlm_baseline_count(m, n_video, n_frames, grid_h, grid_w, keep_budget, stride_h, stride_w)
+    if count < 0:
+        raise SpecVLMError("specvlm_baseline_count", count)
+    keep_idx = torch.empty(count, dtype=torch.int32, device=device or "cuda")
+    need = lib().specvlm_baseline_workspace_bytes(m, n_video)
+    if need:
+        workspace = _ws(workspace, need, keep_idx)
+    rc = lib().specvlm_baseline_keep(m, n_video, n_frames, grid_h, grid_w, keep_budget, stride_h, stride_w,
+                                     seed, _ptr(keep_idx), _ptr(workspace),
+                                     workspace.numel() if workspace is not None else 0, _stream())
+    _check("specvlm_baseline_keep", rc)
+    return keep_idx
