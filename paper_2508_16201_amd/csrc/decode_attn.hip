@@ -54,7 +54,6 @@ struct AttnParams {
     float* part_ml;          // [batch*H_kv][num_splits][rows_pad][2] (running max in log2 units, sum)
     int rows_pad;
     int n_work;
-    int heads_fastest;
     const uint64_t* block_mask;  // [sum q_len] tree masks of the block's queries, or null (chain)
 };
 
@@ -114,7 +113,7 @@ template <int D> struct ValueVec;
 template <> struct ValueVec<128> { typedef u32x4 type; };
 template <> struct ValueVec<64>  { typedef u32x2 type; };
 
-template <int D, int MB, int KS, int TK, int NS>
+template <int D, int MB, int KS, int TK, int NS, bool STREAM>
 __global__ __launch_bounds__(MB * KS * kWave)
 void attn_split_kernel(const AttnParams p)
 {
@@ -135,22 +134,16 @@ void attn_split_kernel(const AttnParams p)
     static_assert(NS >= 2 && NS <= 6, "ring depth");
     typedef typename ValueVec<D>::type vvec_t;
 
-    // Dispatch order.  Head-major caches: consecutive workgroups are consecutive
-    // splits of one (request, head).  Token-major caches interleave the heads
-    // inside every token row, so the kv heads of one (request, split) are made
-    // neighbours: they start together and walk the same DRAM pages at the same
-    // time.  Either way a request is spread over all XCDs (ragged batches stay
-    // balanced; the merge reads the partials through HBM anyway).
+    // Dispatch order: the kv heads of one (request, split) are neighbours.  Workgroups are dealt
+    // to the XCDs round-robin by id, so with 8 kv heads every split of head g runs on XCD g: its
+    // partial results stay in that XCD's L2, where the merge kernel (same head-to-XCD order) finds
+    // them.  Token-major caches interleave the heads inside every token row, so neighbours also
+    // walk the same DRAM pages at the same time.  A request is spread over all XCDs either way
+    // (ragged batches stay balanced).
     const int vid = blockIdx.x;
-    int split, bh;
-    if (p.heads_fastest) {
-        const int g_ = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
-        split = rest % p.num_splits;
-        bh = (rest / p.num_splits) * p.n_kv_heads + g_;
-    } else {
-        split = vid % p.num_splits;
-        bh = vid / p.num_splits;
-    }
+    const int g_ = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
+    const int split = rest % p.num_splits;
+    const int bh = (rest / p.num_splits) * p.n_kv_heads + g_;
     const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
 
     int q0 = 0, ql = p.q_len, kv0 = 0, kvl = p.kv_len;
@@ -214,7 +207,9 @@ void attn_split_kernel(const AttnParams p)
             const int chunk = is_v ? ld_chunk : (ld_chunk ^ swz);
             const char* src = (is_v ? vbase : kbase) + (key * tok_bytes + (uint32_t)chunk * 16u);
             unsigned char* dst = st + n * 1024;     // + lane * 16 by the hardware
-            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src, (SPECVLM_AS3 void*)dst, 16, 0, 0);
+            // a large cache is read once per launch: non-temporal, so it does not displace what is reused;
+            // a small one (the draft's pruned cache, re-read every decode step) stays cacheable
+            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src, (SPECVLM_AS3 void*)dst, 16, 0, STREAM ? 2 : 0);
         }
     };
 
@@ -245,13 +240,6 @@ void attn_split_kernel(const AttnParams p)
                 s0 = mfma16(__builtin_bit_cast(bf16x8, k0), qf[kk], s0);
                 s1 = mfma16(__builtin_bit_cast(bf16x8, k1), qf[kk], s1);
             }
-            // values of the lane's 8 keys: 4c+i (i<4) and 16+4c+(i-4)
-            vvec_t vr[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int kl = chunk * kChunkKeys + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
-                vr[i] = *reinterpret_cast<const vvec_t*>(vt_lds + kl * ROW_BYTES + r * (DJ * 2));
-            }
             float s[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) { s[i] = s0[i] * p.scale_log2; s[4 + i] = s1[i] * p.scale_log2; }
@@ -265,6 +253,13 @@ void attn_split_kernel(const AttnParams p)
                     const bool in_block_hidden = bk >= 0 && ((word >> (bk & 31)) & 1u) == 0u;
                     s[i] = (key >= k_end || in_block_hidden) ? -INFINITY : s[i];
                 }
+            }
+            // values of the lane's 8 keys: 4c+i (i<4) and 16+4c+(i-4)
+            vvec_t vr[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int kl = chunk * kChunkKeys + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
+                vr[i] = *reinterpret_cast<const vvec_t*>(vt_lds + kl * ROW_BYTES + r * (DJ * 2));
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
                              fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -422,7 +417,9 @@ void attn_merge_kernel(const AttnParams p)
     __shared__ float s_w[kMaxSplits];
     __shared__ float s_red[8];
     __shared__ __align__(16) float s_acc[GROUPS][D];
-    const int row = blockIdx.x, bh = blockIdx.y;
+    // (request, kv head) fastest: workgroup id modulo the XCD count follows the kv head, as in the split kernel
+    const int nbh = p.batch * p.n_kv_heads;
+    const int bh = blockIdx.x % nbh, row = blockIdx.x / nbh;
     const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
     int q0 = 0, ql = p.q_len, kvl = p.kv_len;
     if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
@@ -492,20 +489,23 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
     const int max_by_len = (kv_len + 127) / 128;              // at least two tiles per split
     int s = num_splits;
     if (s <= 0) {
-        // one workgroup per CU when the (request, head) pairs are few; for many
-        // pairs (ragged batches) cap a split at 2048 keys so that long and short
-        // requests decompose into similar pieces the dispatcher can balance
         const int heads = batch * n_kv_heads;
-        const int fill = (kNumCu + heads - 1) / heads;
-        const int by_len = (kv_len + 2047) / 2048;
-        s = fill > by_len ? fill : by_len;
-        // two workgroups are resident per CU (64 KB of LDS ring each): when the
-        // launch needs several rounds, make it a whole number of rounds
-        const int slots = 2 * kNumCu;
-        if (heads * s > slots && slots % heads == 0) {
-            const int unit = slots / heads;
-            s = ((s + unit / 2) / unit) * unit;
-            if (s < unit) s = unit;
+        // One request: exactly one round of workgroups, one per CU.  Every workgroup then streams
+        // the same share from start to end; more, smaller splits only add partial results and
+        // rounds (measured: 131K keys run at 5.9 TB/s with 32 splits per head, 4.7 TB/s with 128).
+        s = (kNumCu + heads - 1) / heads;
+        if (batch > 1) {
+            // Ragged batches: cap a split at 2048 keys so that long and short requests decompose
+            // into similar pieces the dispatcher can balance; two workgroups are resident per CU
+            // (64 KB of LDS ring each), and a launch of several rounds is made a whole number of them.
+            const int by_len = (kv_len + 2047) / 2048;
+            if (by_len > s) s = by_len;
+            const int slots = 2 * kNumCu;
+            if (heads * s > slots && slots % heads == 0) {
+                const int unit = slots / heads;
+                s = ((s + unit / 2) / unit) * unit;
+                if (s < unit) s = unit;
+            }
         }
     }
     if (s > max_by_len) s = max_by_len;
@@ -514,8 +514,8 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
     return s;
 }
 
-template <int D, int MB, int KS, int TK, int NS>
-static int launch_attn(const AttnParams& p, hipStream_t stream)
+template <int D, int MB, int KS, int TK, int NS, bool STREAM>
+static int launch_attn_s(const AttnParams& p, hipStream_t stream)
 {
     constexpr int NW = MB * KS;
     constexpr size_t ring = (size_t)NS * 2 * TK * D * 2;
@@ -524,20 +524,32 @@ static int launch_attn(const AttnParams& p, hipStream_t stream)
     if (lds > 64 * 1024) {
         static bool raised = false;
         if (!raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS, STREAM>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return SPECVLM_ELAUNCH;
             raised = true;
         }
     }
-    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS>), dim3(p.n_work), dim3(NW * kWave),
+    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, STREAM>), dim3(p.n_work), dim3(NW * kWave),
                        lds, stream, p);
     return launch_status();
+}
+
+// Caches above this size per launch cannot live in the last-level cache between launches anyway.
+constexpr int64_t kStreamBytes = 32ll << 20;
+
+template <int D, int MB, int KS, int TK, int NS>
+static int launch_attn(const AttnParams& p, hipStream_t stream)
+{
+    const int64_t kv_bytes = 2ll * p.batch * p.n_kv_heads * (int64_t)p.kv_len * D * 2;
+    return kv_bytes >= kStreamBytes ? launch_attn_s<D, MB, KS, TK, NS, true>(p, stream)
+                                    : launch_attn_s<D, MB, KS, TK, NS, false>(p, stream);
 }
 
 template <int D>
 static int launch_attn_d(const AttnParams& p, int mb, hipStream_t stream)
 {
+
     // (key-split waves, tile keys, ring depth) per row-block count; the ring
     // holds NS * 2 * TK * D * 2 bytes of LDS.
     switch (mb) {
@@ -610,7 +622,6 @@ static int attn_impl(
     p.split_keys = (kv_len + p.num_splits - 1) / p.num_splits;
     p.rows_pad = mb * 16;
     p.n_work = batch * n_kv_heads * p.num_splits;
-    p.heads_fastest = (kv_tok_stride > kv_head_stride) ? 1 : 0;
     p.part_o = nullptr; p.part_ml = nullptr;
     if (p.num_splits > 1) {
         const size_t need = specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads,
@@ -624,7 +635,7 @@ static int attn_impl(
     int rc = head_dim == 128 ? launch_attn_d<128>(p, mb, s) : launch_attn_d<64>(p, mb, s);
     if (rc != SPECVLM_OK) return rc;
     if (p.num_splits > 1) {
-        dim3 grid(rows, batch * n_kv_heads);
+        dim3 grid(rows * batch * n_kv_heads);
         if (head_dim == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 4>), grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL((attn_merge_kernel<64, 4>), grid, dim3(256), 0, s, p);
         rc = launch_status();
