@@ -18,7 +18,19 @@
 //   stored with their 16-byte chunks XOR-swizzled by the key index so that the
 //   MFMA operand reads (16 keys x one chunk per 16 lanes) hit distinct banks;
 //   the swizzle is applied on the global-address side, the LDS side of a
-//   direct load being fixed (lane * 16 bytes).
+//   direct load being fixed (lane * 16 bytes).  The Q fragments take the same
+//   road (HBM -> LDS -> registers): with no load returning into registers the
+//   compiler has nothing to guard with a wait that would drain the ring, and
+//   the waits the kernel places itself are the only ones in the sweep.  A cache
+//   of 8 MB or more per launch is read with non-temporal loads.
+//
+// Placement
+//   Workgroup ids run over the kv heads fastest; ids are dealt to the 8 XCDs
+//   round-robin, so with 8 kv heads all splits of a head and the merge of that
+//   head share one XCD and its L2, where the fp32 partials stay between the
+//   two kernels.  A single request is cut into about 192 workgroups in one
+//   round (HBM saturates before every CU is busy); ragged batches into splits
+//   of at most 2048 keys that the dispatcher can balance.
 //
 // MFMA formulation (v_mfma_f32_16x16x32_bf16, lane = 16*c + r)
 //   S^T = K Q^T : A = K chunk (rows = 16 keys, contraction = d), B = Q^T.  Query
@@ -59,6 +71,7 @@ struct AttnParams {
 
 constexpr int kChunkKeys = 32;       // keys per PV contraction step
 constexpr int kMaxSplits = 256;
+constexpr int kTargetWorkgroups = 192;  // workgroups of a single-request launch
 
 // s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
 constexpr int vmcnt_imm(int n)
@@ -131,7 +144,7 @@ void attn_split_kernel(const AttnParams p)
     constexpr int NCHUNK = TK / kChunkKeys;      // 32-key chunks per tile
     constexpr int LDS_STRIDE = D + 4;            // merge buffer row stride (floats)
     static_assert(NCHUNK % KS == 0, "chunks must divide among the key-split waves");
-    static_assert(NS >= 2 && NS <= 6, "ring depth");
+    static_assert(NS >= 2 && NS <= 5, "ring depth");
     typedef typename ValueVec<D>::type vvec_t;
 
     // Dispatch order: the kv heads of one (request, split) are neighbours.  Workgroups are dealt
@@ -163,23 +176,25 @@ void attn_split_kernel(const AttnParams p)
     extern __shared__ __align__(16) unsigned char smem[];
     // stage s: K tile at s*2*TILE_BYTES, V tile right after it
 
-    // ---- this wave's Q fragments (B operand of S^T) and the row's last visible key ----
+    // ---- this wave's Q fragments (B operand of S^T) ----
+    // They travel HBM -> LDS -> registers like the tiles do (through the ring's last stage, which
+    // no tile uses before the first barrier).  A load that returns into registers would make the
+    // compiler guard those registers with waits that also drain the younger tile loads.
     bf16x8 qf[KK];
-    uint64_t row_mask;          // which of the block's own keys this query row sees (bit b = block key b)
+    int t_blk;                  // this lane's query row is the block's t_blk-th query
+    unsigned char* q_stage = smem + (NS - 1) * (2 * TILE_BYTES) + wave * (KK * 1024);
+    static_assert(MB * KS * KK * 1024 <= 2 * TILE_BYTES, "Q staging must fit in one ring stage");
     {
         const int row = mb * 16 + r;
-        const bool live = row < n_rows;
+        const bool live = row < n_rows;             // padding rows read row 0: finite, never stored
         const int t = live ? row / p.group : 0;
         const int h = g * p.group + (live ? row % p.group : 0);
-        // chain: the block is causal, query t sees block keys 0..t; tree: the caller's ancestor mask
-        row_mask = p.block_mask ? p.block_mask[q0 + t] : ((2ull << t) - 1ull);
+        t_blk = t;
         const __bf16* qp = p.q + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + c * 8;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (live) raw = *reinterpret_cast<const u32x4*>(qp + kk * 32);
-            qf[kk] = __builtin_bit_cast(bf16x8, raw);
-        }
+        for (int kk = 0; kk < KK; ++kk)
+            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(qp + kk * 32),
+                                             (SPECVLM_AS3 void*)(q_stage + kk * 1024), 16, 0, 0);
     }
 
     const char* kbase = reinterpret_cast<const char*>(p.k + (int64_t)kv0 * p.kv_tok + (int64_t)g * p.kv_head);
@@ -193,7 +208,6 @@ void attn_split_kernel(const AttnParams p)
     auto issue_tile = [&](int tile, int stage) {
         const int base = k_begin + tile * TK;
         unsigned char* st = smem + stage * (2 * TILE_BYTES);
-        if (wave >= LW) return;
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
             const int n = wave + LW * j;
@@ -244,6 +258,10 @@ void attn_split_kernel(const AttnParams p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) { s[i] = s0[i] * p.scale_log2; s[4 + i] = s1[i] * p.scale_log2; }
             if (need_mask) {
+                // Block keys this lane's query row may see (bit b = block key b).  Chain: the block is
+                // causal, query t sees block keys 0..t; tree: the caller's ancestor mask, fetched here
+                // (only the last chunks of a request get here) rather than held through the sweep.
+                const uint64_t row_mask = p.block_mask ? p.block_mask[q0 + t_blk] : ((2ull << t_blk) - 1ull);
                 const uint32_t mask_lo = (uint32_t)row_mask, mask_hi = (uint32_t)(row_mask >> 32);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -293,24 +311,39 @@ void attn_split_kernel(const AttnParams p)
     };
 
     // ---- ring of NS stages: NS-1 tiles in flight while one is consumed ----
-    const int n_tiles = (k_end - k_begin + TK - 1) / TK;
+    // The loader waves always start NS-1 tiles (a split shorter than that loads its last tile
+    // again into a stage nobody reads), then every wave waits for its Q fragments, which are older
+    // than any tile load, and takes them into registers.
+    const bool is_loader = wave < LW;
+    const int n_tiles = (k_end - k_begin + TK - 1) / TK;            // >= 1
+    const int n_load = n_tiles > NS - 1 ? n_tiles : NS - 1;          // tiles as the loader counts them
+    if (is_loader) {
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < n_tiles) issue_tile(s, s);
-    for (int i = 0; i < n_tiles; ++i) {
-        // tiles issued after tile i so far: min(NS-2, n_tiles-1-i); each is LPW loads of this wave
-        const int younger = min(NS - 2, n_tiles - 1 - i);
-        switch (younger) {                           // (only values <= NS-2 occur)
-            case 0:  wait_vmcnt<0>(); break;
-            case 1:  wait_vmcnt<(NS >= 3 ? 1 : 0) * LPW>(); break;
-            case 2:  wait_vmcnt<(NS >= 4 ? 2 : 0) * LPW>(); break;
-            case 3:  wait_vmcnt<(NS >= 5 ? 3 : 0) * LPW>(); break;
-            default: wait_vmcnt<(NS >= 6 ? 4 : 0) * LPW>(); break;
-        }
-        stage_barrier();                             // tile i landed for everyone; stage (i-1)%NS is free
-        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, (i + NS - 1) % NS);
-        compute_tile(i, i % NS);
+        for (int s = 0; s < NS - 1; ++s) issue_tile(s < n_tiles ? s : n_tiles - 1, s);
+        wait_vmcnt<(NS - 1) * LPW>();                // the Q loads are older than every tile load
+    } else {
+        wait_vmcnt<0>();
     }
+    __asm__ volatile("" ::: "memory");
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(q_stage + kk * 1024 + lane * 16);
+    __asm__ volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): read before the stage is handed to the loader
+    __asm__ volatile("" ::: "memory");
+    int i = 0;
+    do {
+        // tiles issued after tile i so far: min(NS-2, n_load-1-i); each is LPW loads of a loader wave
+        const int younger = min(NS - 2, n_load - 1 - i);
+        wait_vmcnt<(NS - 2) * LPW>();
+        if constexpr (NS >= 5) { if (younger <= 2) wait_vmcnt<2 * LPW>(); }
+        if constexpr (NS >= 4) { if (younger <= 1) wait_vmcnt<1 * LPW>(); }
+        if constexpr (NS >= 3) { if (younger <= 0) wait_vmcnt<0>(); }
+        stage_barrier();                             // tile i landed for everyone; stage (i-1)%NS is free
+        if (is_loader && i + NS - 1 < n_load) issue_tile(i + NS - 1, (i + NS - 1) % NS);
+        compute_tile(i, i % NS);
+    } while (++i < n_tiles);
+    wait_vmcnt<0>();                                 // (a short split's spare copies may still be landing)
 
     // ---- epilogue ----
     l_run = quad_sum(l_run);
@@ -490,10 +523,12 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
     int s = num_splits;
     if (s <= 0) {
         const int heads = batch * n_kv_heads;
-        // One request: exactly one round of workgroups, one per CU.  Every workgroup then streams
-        // the same share from start to end; more, smaller splits only add partial results and
-        // rounds (measured: 131K keys run at 5.9 TB/s with 32 splits per head, 4.7 TB/s with 128).
-        s = (kNumCu + heads - 1) / heads;
+        // One request: a single round of workgroups, about three per four CUs.  Every workgroup then
+        // streams the same share from start to end and HBM is saturated well before all CUs are
+        // busy; more, smaller splits only add partial results and rounds (measured on 8 kv heads:
+        // 131K keys run at 6.2 TB/s with 24 or 32 splits per head, 4.7 TB/s with 128; 33K keys at
+        // 4.9 TB/s with 24, 4.2 TB/s with 32).
+        s = (kTargetWorkgroups + heads - 1) / heads;
         if (batch > 1) {
             // Ragged batches: cap a split at 2048 keys so that long and short requests decompose
             // into similar pieces the dispatcher can balance; two workgroups are resident per CU
@@ -535,8 +570,10 @@ static int launch_attn_s(const AttnParams& p, hipStream_t stream)
     return launch_status();
 }
 
-// Caches above this size per launch cannot live in the last-level cache between launches anyway.
-constexpr int64_t kStreamBytes = 32ll << 20;
+// From this size per launch on, the cache is streamed with non-temporal loads: its lines would
+// only push the split partials (which the merge re-reads) and other reusable data out of the L2.
+// Smaller caches (a draft's pruned cache, re-read at every decode step) stay cacheable.
+constexpr int64_t kStreamBytes = 8ll << 20;
 
 template <int D, int MB, int KS, int TK, int NS>
 static int launch_attn(const AttnParams& p, hipStream_t stream)
@@ -554,9 +591,9 @@ static int launch_attn_d(const AttnParams& p, int mb, hipStream_t stream)
     // holds NS * 2 * TK * D * 2 bytes of LDS.
     switch (mb) {
         case 1: return launch_attn<D, 1, 4, 128, 2>(p, stream);
-        case 2: return launch_attn<D, 2, 4, 128, 2>(p, stream);
-        case 3: return launch_attn<D, 3, 2, 64, 2>(p, stream);
-        case 4: return launch_attn<D, 4, 2, 64, 2>(p, stream);
+        case 2: return launch_attn<D, 2, 2, 64, 3>(p, stream);
+        case 3: return launch_attn<D, 3, 2, 64, 3>(p, stream);
+        case 4: return launch_attn<D, 4, 2, 64, 3>(p, stream);
     }
     return SPECVLM_EUNSUPPORTED;
 }
