@@ -1,8 +1,9 @@
 /*
  * specvlm.h -- C ABI of the SpecVLM speculative-decode hot path on MI355X.
  *
- * Five operations, one per step of a speculative decode step of a video LLM
- * over a long video KV cache (paper: arXiv 2508.16201):
+ * One operation per step of a speculative decode step of a video LLM over a
+ * long video KV cache (paper: arXiv 2508.16201), and the variants of them the
+ * paper's tree decoding and ablations need:
  *
  *   specvlm_score        language-to-video attention scores   (Sec. 3.1, Eq. 4-5)
  *   specvlm_select       Stage I top-k + Stage II uniform stride (Sec. 3.2, Eq. 6-7)
@@ -11,6 +12,7 @@
  *   specvlm_decode_attn  draft decode / parallel verification  (Sec. 2.1)
  *   specvlm_accept       draft-token acceptance                (Sec. 2.1; App. A greedy)
  *   specvlm_tree_attn / specvlm_accept_tree   the same two steps for a draft tree (App. B)
+ *   specvlm_baseline_keep  retention sets of the attention-agnostic pruners (Sec. 2.2, 5.2)
  *
  * Conventions shared by every call
  * --------------------------------
