@@ -438,17 +438,17 @@ void attn_split_kernel(const AttnParams p)
 }
 
 // Merge of the split partials: o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s.
-// One workgroup per (kv head, query row).  All loads of a phase are independent
-// (one split per thread for the statistics, splits strided over thread groups
-// for the outputs), so the kernel costs a few memory round trips, not one per split.
+// One workgroup per (kv head, query row); thread (grp, col) folds the splits grp, grp + GROUPS, ...
+// for 4 output columns.  Every load of the first PRE splits per thread is issued up front, so the
+// kernel costs one memory round trip; each group folds its splits against its own maximum and a
+// single barrier later group 0 combines the GROUPS partial results.
 template <int D, int PRE>
 __global__ __launch_bounds__(256)
 void attn_merge_kernel(const AttnParams p)
 {
     constexpr int TPR = D / 4;                       // threads that cover one row of D columns
     constexpr int GROUPS = 256 / TPR;                // split groups working in parallel
-    __shared__ float s_w[kMaxSplits];
-    __shared__ float s_red[8];
+    __shared__ float s_m[GROUPS], s_l[GROUPS];
     __shared__ __align__(16) float s_acc[GROUPS][D];
     // (request, kv head) fastest: workgroup id modulo the XCD count follows the kv head, as in the split kernel
     const int nbh = p.batch * p.n_kv_heads;
@@ -460,58 +460,65 @@ void attn_merge_kernel(const AttnParams p)
     if (ql <= 0 || kvl < ql || row >= p.group * ql) return;
     const int live = min(p.num_splits, (kvl + p.split_keys - 1) / p.split_keys);
     const int64_t slot0 = (int64_t)bh * p.num_splits * p.rows_pad + row;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    // All loads are issued up front (one round trip): one split's statistics
-    // per thread, and this thread's 4 columns of up to PRE splits of its group.
+    const int tid = threadIdx.x;
     const int grp = tid / TPR, col = (tid % TPR) * 4;
-    float m_s = -INFINITY, l_s = 0.f;
-    if (tid < live) {
-        const float* ml = p.part_ml + (slot0 + (int64_t)tid * p.rows_pad) * 2;
-        m_s = ml[0]; l_s = ml[1];
-    }
-    floatx4 ov[PRE > 0 ? PRE : 1];
-#pragma unroll
-    for (int i = 0; i < PRE; ++i) {
-        const int s = grp + GROUPS * i;
-        ov[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (s < live)
-            ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + (slot0 + (int64_t)s * p.rows_pad) * D + col);
-    }
-    float m = m_s;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-    if (lane == 0) s_red[wave] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-    const float m_ref = (m == -INFINITY) ? 0.f : m;
-    const float w_s = (tid < live) ? fast_exp2(m_s - m_ref) : 0.f;
-    s_w[tid] = w_s;
-    float l = w_s * l_s;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
-    if (lane == 0) s_red[4 + wave] = l;
-    __syncthreads();
-    l = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
 
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float m_i[PRE], l_i[PRE];
+    floatx4 ov[PRE];
 #pragma unroll
     for (int i = 0; i < PRE; ++i) {
         const int s = grp + GROUPS * i;
-        if (s < live) acc += s_w[s] * ov[i];
+        m_i[i] = -INFINITY; l_i[i] = 0.f; ov[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (s < live) {
+            const int64_t slot = slot0 + (int64_t)s * p.rows_pad;
+            const float* ml = p.part_ml + slot * 2;          // the same address across the group: one transaction
+            m_i[i] = ml[0]; l_i[i] = ml[1];
+            ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+        }
     }
-    for (int s = grp + GROUPS * PRE; s < live; s += GROUPS)
-        acc += s_w[s] * *reinterpret_cast<const floatx4*>(
-                            p.part_o + (slot0 + (int64_t)s * p.rows_pad) * D + col);
+    float m_loc = m_i[0];
+#pragma unroll
+    for (int i = 1; i < PRE; ++i) m_loc = fmaxf(m_loc, m_i[i]);
+    float m_ref = (m_loc == -INFINITY) ? 0.f : m_loc;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l_loc = 0.f;
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const float w = fast_exp2(m_i[i] - m_ref);           // 0 for an absent or empty split
+        acc += w * ov[i];
+        l_loc += w * l_i[i];
+    }
+    for (int s = grp + GROUPS * PRE; s < live; s += GROUPS) {   // more splits than the prefetch covers
+        const int64_t slot = slot0 + (int64_t)s * p.rows_pad;
+        const float m_s = p.part_ml[slot * 2], l_s = p.part_ml[slot * 2 + 1];
+        const floatx4 o_s = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+        const float m_new = fmaxf(m_loc, m_s);
+        const float r_new = (m_new == -INFINITY) ? 0.f : m_new;
+        const float f_old = fast_exp2(m_loc - r_new), f_s = fast_exp2(m_s - r_new);
+        acc = acc * f_old + f_s * o_s;
+        l_loc = l_loc * f_old + f_s * l_s;
+        m_loc = m_new;
+    }
     *reinterpret_cast<floatx4*>(&s_acc[grp][col]) = acc;
+    if (col == 0) { s_m[grp] = m_loc; s_l[grp] = l_loc; }
     __syncthreads();
     if (grp != 0) return;
+    float m = s_m[0];
 #pragma unroll
-    for (int gg = 1; gg < GROUPS; ++gg) acc += *reinterpret_cast<const floatx4*>(&s_acc[gg][col]);
-    acc *= 1.f / l;
+    for (int gg = 1; gg < GROUPS; ++gg) m = fmaxf(m, s_m[gg]);
+    m_ref = (m == -INFINITY) ? 0.f : m;
+    floatx4 tot = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+#pragma unroll
+    for (int gg = 0; gg < GROUPS; ++gg) {
+        const float f = fast_exp2(s_m[gg] - m_ref);
+        tot += f * *reinterpret_cast<const floatx4*>(&s_acc[gg][col]);
+        l += f * s_l[gg];
+    }
+    tot *= 1.f / l;
     const int t = row / p.group, h = g * p.group + row % p.group;
     __bf16* op = p.out + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + col;
-    *reinterpret_cast<bf16x4*>(op) = __builtin_convertvector(acc, bf16x4);
+    *reinterpret_cast<bf16x4*>(op) = __builtin_convertvector(tot, bf16x4);
     if (p.lse && col == 0)
         p.lse[(int64_t)(q0 + t) * p.n_q_heads + h] = (m + fast_log2(l)) * kLn2;
 }
@@ -673,7 +680,7 @@ static int attn_impl(
     if (rc != SPECVLM_OK) return rc;
     if (p.num_splits > 1) {
         dim3 grid(rows * batch * n_kv_heads);
-        if (head_dim == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 4>), grid, dim3(256), 0, s, p);
+        if (head_dim == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 6>), grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL((attn_merge_kernel<64, 4>), grid, dim3(256), 0, s, p);
         rc = launch_status();
     }
