@@ -15,6 +15,7 @@ namespace specvlm {
 constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
 constexpr int kAccChunk = 8192;        // vocab entries per pass-1 workgroup
+constexpr int kAccPerThread = kAccChunk / 256;   // of which each of the 256 threads takes this many
 
 struct AcceptParams {
     const float* target;      // [batch, gamma+1, vocab]
@@ -44,10 +45,18 @@ void accept_argmax_partial(const AcceptParams p)
     const int chunk = blockIdx.x, row = blockIdx.y, b = blockIdx.z;
     const float* x = p.target + ((int64_t)b * (p.gamma + 1) + row) * p.vocab;
     const int lo = chunk * kAccChunk, hi = min(p.vocab, lo + kAccChunk);
+    // the thread's whole share is requested before the first value is looked at: one round trip
+    float y[kAccPerThread];
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) {
+        const int v = lo + j * 256 + threadIdx.x;
+        y[j] = v < hi ? x[v] : 0.f;
+    }
     float bv = 0.f; int bi = -1;
-    for (int v = lo + threadIdx.x; v < hi; v += 256) {
-        const float y = x[v];
-        if (bi < 0 || y > bv) { bv = y; bi = v; }     // ascending v: first maximum is kept
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) {
+        const int v = lo + j * 256 + threadIdx.x;
+        if (v < hi && (bi < 0 || y[j] > bv)) { bv = y[j]; bi = v; }     // ascending v: first maximum is kept
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -100,8 +109,16 @@ void accept_softmax_partial(const AcceptParams p)
         ? p.target + ((int64_t)b * (p.gamma + 1) + row) * p.vocab
         : p.draft + ((int64_t)b * p.gamma + (row - p.gamma - 1)) * p.vocab;
     const int lo = chunk * kAccChunk, hi = min(p.vocab, lo + kAccChunk);
+    // the thread's whole share is requested up front and kept for the second pass
+    float y[kAccPerThread];
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) {
+        const int v = lo + j * 256 + threadIdx.x;
+        y[j] = v < hi ? x[v] * p.inv_t_log2 : -INFINITY;
+    }
     float m = -INFINITY;
-    for (int v = lo + threadIdx.x; v < hi; v += 256) m = fmaxf(m, x[v] * p.inv_t_log2);
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) m = fmaxf(m, y[j]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -109,7 +126,8 @@ void accept_softmax_partial(const AcceptParams p)
     __syncthreads();
     m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
     float z = 0.f;
-    for (int v = lo + threadIdx.x; v < hi; v += 256) z += fast_exp2(x[v] * p.inv_t_log2 - m);
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) z += fast_exp2(y[j] - m);       // (-inf padding adds 0)
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) z += __shfl_xor(z, off);
     if (lane == 0) s_z[wave] = z;
@@ -125,12 +143,10 @@ __global__ __launch_bounds__(kAccThreads)
 void accept_sample_final(const AcceptParams p)
 {
     __shared__ float s_m[129], s_z[129];        // merged (max, sum) of up to 2*gamma+1 rows
-    __shared__ float s_w[kAccWaves];
-    __shared__ float s_scan[kAccThreads];
-    __shared__ int s_n, s_y;
+    __shared__ float s_w[kAccWaves], s_w2[kAccWaves];
     __shared__ int s_idx[kAccWaves];
-    __shared__ float s_total;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ int s_n, s_y;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rows = 2 * p.gamma + 1;
     for (int row = tid; row < rows; row += kAccThreads) {
         const int64_t slot = ((int64_t)b * rows + row) * p.n_chunks;
@@ -145,17 +161,22 @@ void accept_sample_final(const AcceptParams p)
     const float* drf = p.draft + (int64_t)b * p.gamma * p.vocab;
     const int32_t* x = p.tokens + (int64_t)b * p.gamma;
     const float* u = p.uniforms + (int64_t)b * (p.gamma + 1);
-    if (tid == 0) {
-        int n = 0;
-        for (; n < p.gamma; ++n) {
-            const int tok = x[n];
-            if (tok < 0 || tok >= p.vocab) break;           // not a token: cannot be accepted
-            const float pt = fast_exp2(tgt[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[n]) / s_z[n];
-            const float qd = fast_exp2(drf[(int64_t)n * p.vocab + tok] * p.inv_t_log2 - s_m[p.gamma + 1 + n]) /
-                             s_z[p.gamma + 1 + n];
-            if (!(u[n] * qd < pt)) break;
+    // The gamma accept tests, one per lane of the first wave (gamma <= 64): every test's loads
+    // are in flight together; the first failing test is found by a ballot.
+    if (wave == 0) {
+        bool ok = true;
+        if (lane < p.gamma) {
+            const int tok = x[lane];
+            ok = tok >= 0 && tok < p.vocab;                      // not a token: cannot be accepted
+            if (ok) {
+                const float pt = fast_exp2(tgt[(int64_t)lane * p.vocab + tok] * p.inv_t_log2 - s_m[lane]) / s_z[lane];
+                const float qd = fast_exp2(drf[(int64_t)lane * p.vocab + tok] * p.inv_t_log2 - s_m[p.gamma + 1 + lane]) /
+                                 s_z[p.gamma + 1 + lane];
+                ok = u[lane] * qd < pt;
+            }
         }
-        s_n = n;
+        const uint64_t failed = __ballot(!ok);
+        if (lane == 0) { s_n = failed ? __ffsll((long long)failed) - 1 : p.gamma; s_y = -1; }
     }
     __syncthreads();
     const int n = s_n;
@@ -171,26 +192,28 @@ void accept_sample_final(const AcceptParams p)
         const float qv = fast_exp2(drow[v] * p.inv_t_log2 - md) * inv_zd;
         return fmaxf(pv - qv, 0.f);
     };
-    // thread t owns the contiguous token range [t*per, (t+1)*per)
-    const int per = (p.vocab + kAccThreads - 1) / kAccThreads;
-    const int lo = min(p.vocab, tid * per), hi = min(p.vocab, lo + per);
+    // Wave w owns the contiguous token segment [w*seg, (w+1)*seg) and reads it 64 consecutive
+    // tokens at a time (coalesced); wave order = token order.
+    const int seg = ((p.vocab + kAccWaves - 1) / kAccWaves + 63) & ~63;
+    const int lo = min(p.vocab, wave * seg), hi = min(p.vocab, lo + seg);
     float mine = 0.f;
-    for (int v = lo; v < hi; ++v) mine += weight(v);
-    // exclusive prefix of the per-thread masses (thread order = token order)
-    s_scan[tid] = mine;
+#pragma unroll 8
+    for (int v = lo + lane; v < hi; v += 64) mine += weight(v);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
+    if (lane == 0) s_w[wave] = mine;
     __syncthreads();
-    if (tid == 0) {
-        float acc = 0.f;
-        for (int t = 0; t < kAccThreads; ++t) { const float y = s_scan[t]; s_scan[t] = acc; acc += y; }
-        s_total = acc;
-        s_y = -1;
+    float before = 0.f, W = 0.f;
+#pragma unroll
+    for (int w = 0; w < kAccWaves; ++w) {
+        const float y = s_w[w];
+        if (w < wave) before += y;
+        W += y;
     }
-    __syncthreads();
-    const float W = s_total;
     if (!(W > 0.f)) {
         // no residual mass (p == q): fall back to the target's most likely token
         float bv = 0.f; int bi = -1;
-        for (int v = lo; v < hi; ++v) {
+        for (int v = lo + lane; v < hi; v += 64) {
             const float y = trow[v];
             if (bi < 0 || y > bv) { bv = y; bi = v; }
         }
@@ -200,7 +223,8 @@ void accept_sample_final(const AcceptParams p)
             const int oi = __shfl_xor(bi, off);
             argmax_merge(bv, bi, ov, oi);
         }
-        if ((tid & 63) == 0) { s_w[tid >> 6] = bv; s_idx[tid >> 6] = bi; }
+        __syncthreads();                                         // every wave has read s_w
+        if (lane == 0) { s_w[wave] = bv; s_idx[wave] = bi; }
         __syncthreads();
         if (tid == 0) {
             for (int w = 1; w < kAccWaves; ++w) argmax_merge(bv, bi, s_w[w], s_idx[w]);
@@ -208,29 +232,60 @@ void accept_sample_final(const AcceptParams p)
         }
         __syncthreads();
     } else {
+        // The owner of the goal is the LAST wave with mass whose prefix does not exceed it: exactly
+        // one wave, whatever rounding did to the sums (a goal that rounding put at or beyond the
+        // total lands on the last wave with mass).  The search then descends once more: the owner's
+        // segment is dealt to all waves again, and the owner of that level walks its few hundred
+        // tokens 64 at a time for the first token whose cumulative mass passes the goal, else takes
+        // its last token with mass.
         const float goal = u[p.gamma] * W;
-        const float before = s_scan[tid];
-        const float after = (tid + 1 < kAccThreads) ? s_scan[tid + 1] : W;
-        // the owner of the goal: the thread whose mass interval [before, after) holds it
-        if (mine > 0.f && before <= goal && goal < after) {
-            float c = before; int y = -1, last = -1;
-            for (int v = lo; v < hi; ++v) {
-                const float w = weight(v);
-                if (w > 0.f) last = v;
-                if (c + w > goal) { y = v; break; }
-                c += w;
+        auto owner_of = [&](const float* mass, float start, float& prefix) {
+            int owner = -1;
+            float acc = start;
+            prefix = start;
+#pragma unroll
+            for (int w = 0; w < kAccWaves; ++w) {
+                if (mass[w] > 0.f && acc <= goal) { owner = w; prefix = acc; }
+                acc += mass[w];
             }
-            atomicMax(&s_y, y >= 0 ? y : last);
+            return owner;
+        };
+        float pre1;
+        const int own1 = owner_of(s_w, 0.f, pre1);
+        const int lo1 = min(p.vocab, own1 * seg), hi1 = min(p.vocab, lo1 + seg);
+        const int seg2 = ((hi1 - lo1 + kAccWaves - 1) / kAccWaves + 63) & ~63;
+        const int lo2 = min(hi1, lo1 + wave * seg2), hi2 = min(hi1, lo2 + seg2);
+        float mine2 = 0.f;
+#pragma unroll 4
+        for (int v = lo2 + lane; v < hi2; v += 64) mine2 += weight(v);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mine2 += __shfl_xor(mine2, off);
+        if (lane == 0) s_w2[wave] = mine2;
+        __syncthreads();
+        float pre2;
+        const int own2 = owner_of(s_w2, pre1, pre2);
+        if (wave == own2) {
+            float c = pre2;
+            int y = -1, last = -1;
+#pragma unroll 2
+            for (int base = lo2; base < hi2; base += 64) {       // no early exit: the loads pipeline
+                const int v = base + lane;
+                const float w = v < hi2 ? weight(v) : 0.f;
+                float incl = w;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const float t = __shfl_up(incl, off);
+                    if (lane >= off) incl += t;
+                }
+                const uint64_t massive = __ballot(w > 0.f);
+                const uint64_t passed = __ballot(w > 0.f && c + incl > goal);
+                if (massive) last = base + 63 - __builtin_clzll(massive);
+                if (passed && y < 0) y = base + __ffsll((long long)passed) - 1;
+                c += __shfl(incl, 63);
+            }
+            if (lane == 0) s_y = y >= 0 ? y : last;
         }
         __syncthreads();
-        if (s_y < 0) {
-            // rounding put the goal at or beyond the total: the last token with mass
-            int last = -1;
-            for (int v = lo; v < hi; ++v) if (weight(v) > 0.f) last = v;
-            __syncthreads();
-            if (last >= 0) atomicMax(&s_y, last);
-            __syncthreads();
-        }
     }
     if (tid == 0) {
         int32_t* out = p.out_tokens + (int64_t)b * (p.gamma + 1);
