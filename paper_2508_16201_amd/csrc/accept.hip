@@ -267,8 +267,7 @@ void accept_sample_final(const AcceptParams p)
         if (wave == own2) {
             float c = pre2;
             int y = -1, last = -1;
-#pragma unroll 2
-            for (int base = lo2; base < hi2; base += 64) {       // no early exit: the loads pipeline
+            for (int base = lo2; base < hi2; base += 64) {       // (at most ten steps at vocab 152 064)
                 const int v = base + lane;
                 const float w = v < hi2 ? weight(v) : 0.f;
                 float incl = w;
