@@ -199,10 +199,12 @@ void score_sweep_kernel(const ScoreParams p)
                 for (int kk = 0; kk < KK; ++kk) acc[sb] = mfma16(af[kk], sf[sb][kk], acc[sb]);
             }
             if (MODE == 0) {
+                // (a zero scale is taken as a vanishing one, so that a masked logit, -inf, times the
+                // scale stays -inf instead of becoming NaN; every other logit still scales to 0)
+                const float sc_a = fmaxf(p.scale_log2, 1e-30f);
                 float tmax[4];
 #pragma unroll
                 for (int sb = 0; sb < 4; ++sb) {
-                    acc[sb] *= p.scale_log2;
                     if (mask) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -210,7 +212,9 @@ void score_sweep_kernel(const ScoreParams p)
                             if (key >= s_end || key > lim[sb]) acc[sb][i] = -INFINITY;
                         }
                     }
-                    tmax[sb] = fmaxf(fmaxf(acc[sb][0], acc[sb][1]), fmaxf(acc[sb][2], acc[sb][3]));
+                    // the logits stay unscaled: the scale (>= 0) is applied to the maximum once and
+                    // rides in the fused multiply-add that forms each exponent
+                    tmax[sb] = fmaxf(fmaxf(acc[sb][0], acc[sb][1]), fmaxf(acc[sb][2], acc[sb][3])) * p.scale_log2;
                 }
                 // rescale only when some row's new maximum outgrows its reference
                 bool grow = false;
@@ -226,8 +230,9 @@ void score_sweep_kernel(const ScoreParams p)
                 }
 #pragma unroll
                 for (int sb = 0; sb < 4; ++sb) {
-                    const float sum = (fast_exp2(acc[sb][0] - m_ref[sb]) + fast_exp2(acc[sb][1] - m_ref[sb])) +
-                                      (fast_exp2(acc[sb][2] - m_ref[sb]) + fast_exp2(acc[sb][3] - m_ref[sb]));
+                    const float sc = sc_a, mr = m_ref[sb];
+                    const float sum = (fast_exp2(fmaf(acc[sb][0], sc, -mr)) + fast_exp2(fmaf(acc[sb][1], sc, -mr))) +
+                                      (fast_exp2(fmaf(acc[sb][2], sc, -mr)) + fast_exp2(fmaf(acc[sb][3], sc, -mr)));
                     l_run[sb] += sum;
                 }
             } else {

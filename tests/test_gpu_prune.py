@@ -61,6 +61,21 @@ def test_score_matches_oracle(B, V, L, P, hq, hkv, d, mode):
     assert_scores_close(got2, want, f"V{V} L{L} mode{mode} row_lse")
 
 
+def test_score_zero_scale_is_the_closed_form(B):
+    """softmax_scale = 0 makes every visible logit 0: mode 1 gives 1/V per token, mode 0 gives
+    mean_i 1/(p_i + 1) (the closed forms that pin the oracle), also where causal masks apply."""
+    V, L, hq, hkv, d = 500, 70, 8, 2, 128
+    q, k = rnd_bits((L, hq, d), 70), rnd_bits((V + L, hkv, d), 71)
+    for pos0 in (V, V - 30):
+        for mode in (0, 1):
+            want = oracle.score(q, k, 0, V, pos0, 0.0, norm_mode=mode)
+            got = B.score(dev_bf16(q), dev_bf16(k), 0, V, pos0, 0.0, norm_mode=mode)
+            torch.cuda.synchronize()
+            assert_scores_close(got, want, f"zero scale mode{mode} pos0 {pos0}")
+    got = B.score(dev_bf16(q), dev_bf16(k), 0, V, V, 0.0, norm_mode=1)
+    np.testing.assert_allclose(host_f64(got), np.full(V, 1.0 / V), rtol=1e-5)
+
+
 def test_score_text_queries_inside_video_span_are_causal(B):
     V, L, hq, hkv, d = 300, 40, 4, 2, 64
     q, k = rnd_bits((L, hq, d), 60), rnd_bits((V + L, hkv, d), 61)
