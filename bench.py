@@ -246,19 +246,28 @@ def main():
     t_layer_us2 = e0.elapsed_time(e1) * 1e3 / (reps * L)
     attn_gbs2 = attn_bytes / (t_layer_us2 * 1e-6) / 1e9
 
-    # The short stages (one or two kernels) replayed back to back: inside a step each of them is
-    # its own graph launch, and the event pair around a lone launch mostly times the launch itself.
-    def replay_us(idx, n=20):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        runners[idx]()
+    # The short stages (one or two kernels): inside a step each is a graph launch of its own, and an
+    # event pair around a lone launch mostly times the launch.  Their GPU time is taken from a graph
+    # that holds the stage ten times over, replayed back to back.
+    def repeated_us(fn, inner=10, outer=5):
+        if args.eager:
+            run = lambda: [fn() for _ in range(inner)]
+        else:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(inner):
+                    fn()
+            run = g.replay
+        run()
         torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        for _ in range(n):
-            runners[idx]()
+        for _ in range(outer):
+            run()
         b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / n
-    short_us = {name: replay_us(i) for i, name in enumerate(stages) if name in ("select", "gather", "accept")}
+        return a.elapsed_time(b) * 1e3 / (inner * outer)
+    short_us = {"select": repeated_us(st_select), "gather": repeated_us(st_gather), "accept": repeated_us(st_accept)}
 
     score_flops = 2.0 * T * hq * d * (V + (T + 1) / 2.0)          # one sweep of the contraction
     score_tflops = score_flops * L / (stage_ms["score"] * 1e-3) / 1e12
