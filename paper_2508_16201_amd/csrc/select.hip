@@ -76,23 +76,30 @@ void select_kernel(const SelectParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int v0 = p.cu_video ? p.cu_video[b] : 0;
     const int n = p.cu_video ? p.cu_video[b + 1] - v0 : p.max_n_video;
+    // The scores are requested first (guarded by the token count alone, so always in bounds); the
+    // request's sizes, one more memory round trip away, are fetched while those loads are in flight.
+    const int per = n > 0 ? (n + kSelThreads - 1) / kSelThreads : 0;
+    const int first = tid * per;
+    const float* sc = p.scores + v0;
+    float raw[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int idx = first + e;
+        raw[e] = (e < per && idx < n) ? sc[idx] : 0.f;
+    }
     const int k = p.k_top[b], budget = p.keep_budget[b];
     const int out0 = p.cu_keep ? p.cu_keep[b] : 0;
     const bool bad = n < 0 || n > E * kSelThreads || k < 0 || k > budget || budget > n;
     if (p.status && tid == 0) p.status[b] = bad ? SPECVLM_EINVAL : SPECVLM_OK;
     if (bad || budget == 0) return;
 
-    const int per = (n + kSelThreads - 1) / kSelThreads;      // <= E
-    const int first = tid * per;
-    const float* sc = p.scores + v0;
-
     uint32_t key[E];
     uint64_t valid = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int idx = first + e;
-        const bool ok = e < per && idx < n;
-        key[e] = ok ? score_key(sc[idx]) : 0u;
+        const bool ok = e < per && idx < n;                     // (per <= E once the sizes are valid)
+        key[e] = ok ? score_key(raw[e]) : 0u;
         if (ok) valid |= 1ull << e;
     }
 
@@ -111,12 +118,16 @@ void select_kernel(const SelectParams p)
                 if (act == 0) continue;
                 const int digit = (key[e] >> shift) & 255;
                 const int leader = __ffsll((long long)act) - 1;
-                const int d0 = __shfl(digit, leader);
+                const int d0 = __builtin_amdgcn_readlane(digit, leader);      // leader is wave-uniform: no LDS crossbar trip
                 const uint64_t same = __ballot(match && digit == d0);
                 if (same == act) {                      // whole wave agrees: one add
                     if (lane == leader) atomicAdd(&s_hist[wave][d0], __popcll(act));
                 } else if (match) {
-                    atomicAdd(&s_hist[wave][digit], 1);
+                    // The 16 per-wave histograms are summed afterwards, so a lane may add to any of
+                    // them: lanes of one instruction that share a digit are spread over all 16 copies
+                    // (an LDS atomic serialises over the lanes that hit one address, and the leading
+                    // digit of attention scores, sign and exponent, takes only a handful of values).
+                    atomicAdd(&s_hist[(wave + lane) & (kSelWaves - 1)][digit], 1);
                 }
             }
             __syncthreads();
