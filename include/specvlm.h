@@ -195,7 +195,13 @@ int specvlm_gather_kv(
  *   lse  optional fp32 [sum q_len_b, H_q]: natural log of each row's softmax sum
  *   q head h reads kv head h / (H_q / H_kv)
  *   num_splits: key-range splits per (request, kv head) (flash-decode);
- *               0 lets the library choose for the shape.
+ *               0 lets the library choose for the shape.  For a batch of 2..64
+ *               requests the choice is made on the device from the request
+ *               lengths: the key tiles of all (request, kv head) pairs are dealt
+ *               in equal contiguous runs to one workgroup per CU, so requests of
+ *               very different lengths finish together.
+ *   Workspace: the query takes the same batch, maxima, head counts and
+ *               num_splits as the call (it is pure: it depends on nothing else).
  * Limits: (H_q/H_kv) * q_len <= 64.
  * -------------------------------------------------------------------------- */
 size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int kv_len,

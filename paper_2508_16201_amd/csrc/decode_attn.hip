@@ -67,9 +67,38 @@ struct AttnParams {
     int rows_pad;
     int n_work;
     const uint64_t* block_mask;  // [sum q_len] tree masks of the block's queries, or null (chain)
+    int balanced;            // batch mode: balanced pieces (see attn_balance) instead of uniform splits
+    int max_wg;              // workgroups launched in balanced mode
+    int tile_keys;           // keys per tile of the split kernel that runs (the unit of balanced mode)
+    int32_t* seg_table;      // balanced mode: per (request, head) {first partial slot, pieces}, written by workgroup 0
 };
 
 constexpr int kChunkKeys = 32;       // keys per PV contraction step
+constexpr int kMaxBalancedBatch = 64;   // (every workgroup walks the request lengths once)
+
+// Tiles of request b in balanced mode; a request with nothing to do (no queries, or fewer keys
+// than queries) has none.
+__device__ __forceinline__ int attn_request_tiles(const AttnParams& p, int b, int tile_keys)
+{
+    const int ql = p.cu_q[b + 1] - p.cu_q[b], kvl = p.cu_kv[b + 1] - p.cu_kv[b];
+    return (ql <= 0 || kvl < ql) ? 0 : (kvl + tile_keys - 1) / tile_keys;
+}
+
+struct AttnBalance { int64_t n_units; int n_wg; };
+
+// Total units (tiles x kv heads over the batch) and the number of workgroups that share them:
+// never more workgroups than units, so every workgroup's run is non-empty and the workgroups that
+// touch a (request, head) are consecutive.
+__device__ __forceinline__ AttnBalance attn_balance(const AttnParams& p, int tile_keys)
+{
+    int64_t n = 0;
+    for (int b = 0; b < p.batch; ++b) n += attn_request_tiles(p, b, tile_keys);
+    n *= p.n_kv_heads;
+    AttnBalance r;
+    r.n_units = n;
+    r.n_wg = (int)min((int64_t)p.max_wg, n);
+    return r;
+}
 constexpr int kMaxSplits = 256;
 constexpr int kTargetWorkgroups = 192;  // workgroups of a single-request launch
 
@@ -147,34 +176,22 @@ void attn_split_kernel(const AttnParams p)
     static_assert(NS >= 2 && NS <= 5, "ring depth");
     typedef typename ValueVec<D>::type vvec_t;
 
-    // Dispatch order: the kv heads of one (request, split) are neighbours.  Workgroups are dealt
-    // to the XCDs round-robin by id, so with 8 kv heads every split of head g runs on XCD g: its
-    // partial results stay in that XCD's L2, where the merge kernel (same head-to-XCD order) finds
-    // them.  Token-major caches interleave the heads inside every token row, so neighbours also
-    // walk the same DRAM pages at the same time.  A request is spread over all XCDs either way
-    // (ragged batches stay balanced).
-    const int vid = blockIdx.x;
-    const int g_ = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
-    const int split = rest % p.num_splits;
-    const int bh = (rest / p.num_splits) * p.n_kv_heads + g_;
-    const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
-
-    int q0 = 0, ql = p.q_len, kv0 = 0, kvl = p.kv_len;
-    if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
-    if (p.cu_kv) { kv0 = p.cu_kv[b]; kvl = p.cu_kv[b + 1] - kv0; }
-    if (ql <= 0 || kvl < ql) return;
-    const int k_begin = split * p.split_keys;
-    if (k_begin >= kvl) return;                     // the merge reads only the live splits
-    const int k_end = min(kvl, k_begin + p.split_keys);
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int mb = wave % MB, ks = wave / MB;
     const int r = lane & 15, c = lane >> 4;
-    const int n_rows = p.group * ql;                // live query rows of this kv head
 
     extern __shared__ __align__(16) unsigned char smem[];
     // stage s: K tile at s*2*TILE_BYTES, V tile right after it
+
+    // One piece of work: keys [k_begin, k_end) of (request b, kv head g) for all its query rows;
+    // the result goes to partial slot slot0 (in units of rows), or straight to the output.
+    auto piece = [&](const int b, const int g, const int k_begin, const int k_end, const int64_t slot0,
+                     const bool direct) {
+    int q0 = 0, ql = p.q_len, kv0 = 0, kvl = p.kv_len;
+    if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
+    if (p.cu_kv) { kv0 = p.cu_kv[b]; kvl = p.cu_kv[b + 1] - kv0; }
+    const int n_rows = p.group * ql;                // live query rows of this kv head
 
     // ---- this wave's Q fragments (B operand of S^T) ----
     // They travel HBM -> LDS -> registers like the tiles do (through the ring's last stage, which
@@ -349,10 +366,10 @@ void attn_split_kernel(const AttnParams p)
     l_run = quad_sum(l_run);
     const int row = mb * 16 + r;
     const int t_row = row / p.group, h_row = g * p.group + row % p.group;
-    const int64_t slot = ((int64_t)bh * p.num_splits + split) * p.rows_pad + row;
+    const int64_t slot = slot0 + row;
     if constexpr (KS == 1) {
         // lane (r, c) holds columns (4c+i)*DJ + j of its row: write them out directly
-        if (p.num_splits == 1) {
+        if (direct) {
             if (row >= n_rows) return;
             const float inv = 1.f / l_run;
             __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head;
@@ -419,7 +436,7 @@ void attn_split_kernel(const AttnParams p)
 #pragma unroll
             for (int qd = 0; qd < CPL / 4; ++qd) acc[qd] += *reinterpret_cast<const floatx4*>(buf + 4 * qd);
         }
-        if (p.num_splits == 1) {
+        if (direct) {
             if (row >= n_rows) return;
             const float inv = 1.f / l_all;
             __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head + col0;
@@ -434,6 +451,76 @@ void attn_split_kernel(const AttnParams p)
             for (int qd = 0; qd < CPL / 4; ++qd) *reinterpret_cast<floatx4*>(po + 4 * qd) = acc[qd];
             if (c == 0 && ks == 0) { p.part_ml[slot * 2] = m_all; p.part_ml[slot * 2 + 1] = l_all; }
         }
+    }
+    };   // piece
+
+    if (!p.balanced) {
+        // Uniform splits.  Dispatch order: the kv heads of one (request, split) are neighbours.
+        // Workgroups are dealt to the XCDs round-robin by id, so with 8 kv heads every split of head
+        // g runs on XCD g: its partial results stay near that XCD, where the merge kernel (same
+        // head-to-XCD order) finds them.  Token-major caches interleave the heads inside every token
+        // row, so neighbours also walk the same DRAM pages at the same time.
+        const int vid = blockIdx.x;
+        const int g = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
+        const int split = rest % p.num_splits;
+        const int b = rest / p.num_splits;
+        int ql = p.q_len, kvl = p.kv_len;
+        if (p.cu_q) ql = p.cu_q[b + 1] - p.cu_q[b];
+        if (p.cu_kv) kvl = p.cu_kv[b + 1] - p.cu_kv[b];
+        if (ql <= 0 || kvl < ql) return;
+        const int k_begin = split * p.split_keys;
+        if (k_begin >= kvl) return;                     // the merge reads only the live splits
+        const int bh = b * p.n_kv_heads + g;
+        piece(b, g, k_begin, min(kvl, k_begin + p.split_keys),
+              ((int64_t)bh * p.num_splits + split) * p.rows_pad, p.num_splits == 1);
+        return;
+    }
+
+    // Balanced pieces for a batch.  The unit of work is one tile of one (request, kv head); the units
+    // are numbered request-major, then head, then tile, and workgroup w takes the contiguous run
+    // [w*T/W, (w+1)*T/W).  A run that crosses from one (request, head) into the next is cut into
+    // pieces there; piece (w, segment) owns partial slot w + segment, which is unique because from
+    // one piece to the next exactly one of the two grows.  Every workgroup derives the same numbers
+    // from the request lengths, as the merge kernel does.
+    const AttnBalance bal = attn_balance(p, TK);
+    const int w = blockIdx.x;
+    if (w == 0) {
+        // the merge kernel's view of the decomposition: for every (request, head) its first partial
+        // slot and the number of pieces (the workgroups that touch it are consecutive; the
+        // workgroup that owns unit x is the largest w with w*T/W <= x)
+        for (int seg = threadIdx.x; seg < p.batch * p.n_kv_heads; seg += MB * KS * kWave) {
+            const int sb = seg / p.n_kv_heads, sg = seg % p.n_kv_heads;
+            int64_t first = 0;
+            for (int bb = 0; bb < sb; ++bb) first += attn_request_tiles(p, bb, TK);
+            const int tiles = attn_request_tiles(p, sb, TK);
+            first = first * p.n_kv_heads + (int64_t)sg * tiles;
+            int w_first = 0, live = 0;
+            if (tiles > 0) {
+                w_first = (int)(((first + 1) * bal.n_wg - 1) / bal.n_units);
+                live = (int)(((first + tiles) * bal.n_wg - 1) / bal.n_units) - w_first + 1;
+            }
+            p.seg_table[2 * seg] = w_first + seg;
+            p.seg_table[2 * seg + 1] = live;
+        }
+    }
+    if (w >= bal.n_wg) return;
+    int64_t x = (int64_t)w * bal.n_units / bal.n_wg;
+    const int64_t x_end = (int64_t)(w + 1) * bal.n_units / bal.n_wg;
+    int b = 0;
+    int64_t base = 0;                                   // first unit of request b
+    while (x < x_end) {
+        int tiles = attn_request_tiles(p, b, TK);
+        while (x >= base + (int64_t)tiles * p.n_kv_heads) {
+            base += (int64_t)tiles * p.n_kv_heads;
+            ++b;
+            tiles = attn_request_tiles(p, b, TK);
+        }
+        const int g = (int)((x - base) / tiles), t = (int)((x - base) % tiles);
+        const int n = (int)min((int64_t)(tiles - t), x_end - x);
+        const int kvl = p.cu_kv[b + 1] - p.cu_kv[b];
+        piece(b, g, t * TK, min(kvl, (t + n) * TK), (int64_t)(w + b * p.n_kv_heads + g) * p.rows_pad, false);
+        x += n;
+        __syncthreads();                                // the next piece reuses the ring and the exchange buffer
     }
 }
 
@@ -458,6 +545,7 @@ void attn_merge_kernel(const AttnParams p)
     if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
     if (p.cu_kv) { kvl = p.cu_kv[b + 1] - p.cu_kv[b]; }
     if (ql <= 0 || kvl < ql || row >= p.group * ql) return;
+    // the partial slots of this (request, head) are consecutive: splits 0..live-1
     const int live = min(p.num_splits, (kvl + p.split_keys - 1) / p.split_keys);
     const int64_t slot0 = (int64_t)bh * p.num_splits * p.rows_pad + row;
     const int tid = threadIdx.x;
@@ -523,7 +611,70 @@ void attn_merge_kernel(const AttnParams p)
         p.lse[(int64_t)(q0 + t) * p.n_q_heads + h] = (m + fast_log2(l)) * kLn2;
 }
 
+// Merge for the balanced decomposition, where a (request, head) has only a handful of pieces: each
+// group of D/4 threads merges one query row on its own, with the loads of up to PRE pieces in
+// flight together, so a workgroup finishes 256 / (D/4) rows and no cross-thread combine is needed.
+template <int D, int PRE>
+__global__ __launch_bounds__(256)
+void attn_merge_rows_kernel(const AttnParams p)
+{
+    constexpr int TPR = D / 4;
+    constexpr int GROUPS = 256 / TPR;
+    const int nbh = p.batch * p.n_kv_heads;
+    const int bh = blockIdx.x % nbh;
+    const int b = bh / p.n_kv_heads, g = bh % p.n_kv_heads;
+    const int tid = threadIdx.x;
+    const int row = (blockIdx.x / nbh) * GROUPS + tid / TPR, col = (tid % TPR) * 4;
+    int q0 = 0, ql = p.q_len, kvl = p.kv_len;
+    if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
+    if (p.cu_kv) { kvl = p.cu_kv[b + 1] - p.cu_kv[b]; }
+    if (ql <= 0 || kvl < ql || row >= p.group * ql) return;
+    const int live = p.seg_table[2 * bh + 1];
+    const int64_t slot0 = (int64_t)p.seg_table[2 * bh] * p.rows_pad + row;
+    float m = -INFINITY, l = 0.f;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < live; s0 += PRE) {
+        float m_i[PRE], l_i[PRE];
+        floatx4 ov[PRE];
+#pragma unroll
+        for (int i = 0; i < PRE; ++i) {
+            m_i[i] = -INFINITY; l_i[i] = 0.f; ov[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (s0 + i < live) {
+                const int64_t slot = slot0 + (int64_t)(s0 + i) * p.rows_pad;
+                m_i[i] = p.part_ml[slot * 2]; l_i[i] = p.part_ml[slot * 2 + 1];
+                ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+            }
+        }
+        float m_new = m;
+#pragma unroll
+        for (int i = 0; i < PRE; ++i) m_new = fmaxf(m_new, m_i[i]);
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float f_old = fast_exp2(m - m_ref);
+        acc *= f_old; l *= f_old;
+#pragma unroll
+        for (int i = 0; i < PRE; ++i) {
+            const float w = fast_exp2(m_i[i] - m_ref);       // 0 for an absent or empty piece
+            acc += w * ov[i];
+            l += w * l_i[i];
+        }
+        m = m_new;
+    }
+    acc *= 1.f / l;
+    const int t = row / p.group, h = g * p.group + row % p.group;
+    __bf16* op = p.out + (int64_t)(q0 + t) * p.q_tok + (int64_t)h * p.q_head + col;
+    *reinterpret_cast<bf16x4*>(op) = __builtin_convertvector(acc, bf16x4);
+    if (p.lse && col == 0)
+        p.lse[(int64_t)(q0 + t) * p.n_q_heads + h] = (m + fast_log2(l)) * kLn2;
+}
+
 // ---------------------------------------------------------------- host side ----
+// A batch whose split count is left to the library is cut into balanced pieces by the kernels
+// themselves (they know the request lengths; the host only knows their maximum).
+static bool attn_is_balanced(int batch, int num_splits)
+{
+    return batch > 1 && batch <= kMaxBalancedBatch && num_splits == 0;
+}
+
 static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
 {
     const int max_by_len = (kv_len + 127) / 128;              // at least two tiles per split
@@ -619,9 +770,16 @@ extern "C" size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int 
     const int rows = (n_q_heads / n_kv_heads) * q_len;
     if (rows > 64) return 0;
     const int rows_pad = round_up(rows, 16);
-    const int splits = choose_splits(batch, kv_len, n_kv_heads, num_splits);
-    if (splits == 1) return 256;
-    const size_t slots = (size_t)batch * n_kv_heads * splits * rows_pad;
+    size_t slots;
+    if (attn_is_balanced(batch, num_splits)) {
+        slots = (size_t)(kNumCu + batch * n_kv_heads) * rows_pad;
+        return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) +
+               align256((size_t)batch * n_kv_heads * 2 * sizeof(int32_t));
+    } else {
+        const int splits = choose_splits(batch, kv_len, n_kv_heads, num_splits);
+        if (splits == 1) return 256;
+        slots = (size_t)batch * n_kv_heads * splits * rows_pad;
+    }
     return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float));
 }
 
@@ -662,23 +820,34 @@ static int attn_impl(
     p.batch = batch; p.q_len = q_len; p.kv_len = kv_len;
     p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = group;
     p.scale_log2 = softmax_scale * kLog2e;
-    p.num_splits = choose_splits(batch, kv_len, n_kv_heads, num_splits);
+    p.balanced = attn_is_balanced(batch, num_splits) ? 1 : 0;
+    p.max_wg = kNumCu;
+    p.tile_keys = mb == 1 ? 128 : 64;                 // TK of the launch shape chosen below
+    p.num_splits = p.balanced ? 2 : choose_splits(batch, kv_len, n_kv_heads, num_splits);
     p.split_keys = (kv_len + p.num_splits - 1) / p.num_splits;
     p.rows_pad = mb * 16;
-    p.n_work = batch * n_kv_heads * p.num_splits;
-    p.part_o = nullptr; p.part_ml = nullptr;
+    p.n_work = p.balanced ? p.max_wg : batch * n_kv_heads * p.num_splits;
+    p.part_o = nullptr; p.part_ml = nullptr; p.seg_table = nullptr;
     if (p.num_splits > 1) {
         const size_t need = specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads,
-                                                                n_kv_heads, head_dim, p.num_splits);
+                                                                n_kv_heads, head_dim, num_splits);
         if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) return SPECVLM_EWORKSPACE;
-        const size_t slots = (size_t)batch * n_kv_heads * p.num_splits * p.rows_pad;
+        const size_t slots = p.balanced ? (size_t)(p.max_wg + batch * n_kv_heads) * p.rows_pad
+                                        : (size_t)batch * n_kv_heads * p.num_splits * p.rows_pad;
         p.part_o = (float*)workspace;
         p.part_ml = (float*)((char*)workspace + align256(slots * head_dim * sizeof(float)));
+        p.seg_table = (int32_t*)((char*)p.part_ml + align256(slots * 2 * sizeof(float)));   // (used in balanced mode)
     }
     hipStream_t s = (hipStream_t)stream;
     int rc = head_dim == 128 ? launch_attn_d<128>(p, mb, s) : launch_attn_d<64>(p, mb, s);
     if (rc != SPECVLM_OK) return rc;
-    if (p.num_splits > 1) {
+    if (p.balanced) {
+        const int per_wg = 256 / (head_dim / 4);
+        dim3 grid((rows + per_wg - 1) / per_wg * batch * n_kv_heads);
+        if (head_dim == 128) hipLaunchKernelGGL((attn_merge_rows_kernel<128, 8>), grid, dim3(256), 0, s, p);
+        else                 hipLaunchKernelGGL((attn_merge_rows_kernel<64, 8>), grid, dim3(256), 0, s, p);
+        rc = launch_status();
+    } else if (p.num_splits > 1) {
         dim3 grid(rows * batch * n_kv_heads);
         if (head_dim == 128) hipLaunchKernelGGL((attn_merge_kernel<128, 6>), grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL((attn_merge_kernel<64, 4>), grid, dim3(256), 0, s, p);

@@ -217,3 +217,38 @@ def test_ragged_batch_of_eight_in_one_launch(B):
     out1 = B.decode_attn(qd, kd, ones, scale, cu_q=cu_q, cu_kv=cu_kv, max_q_len=g1, max_kv_len=max(lens))
     torch.cuda.synchronize()
     assert (out1.float() - 1.0).abs().max().item() <= 2 ** -7
+
+
+def _batch_case(B, lens, q_lens, hq, hkv, d, seed, scale=0.09):
+    qs = [rnd_bits((ql, hq, d), seed + i) for i, ql in enumerate(q_lens)]
+    ks = [rnd_bits((n, hkv, d), seed + 1000 + i) for i, n in enumerate(lens)]
+    vs = [rnd_bits((n, hkv, d), seed + 2000 + i) for i, n in enumerate(lens)]
+    cu_q = torch.tensor(np.concatenate([[0], np.cumsum(q_lens)]), dtype=torch.int32).cuda()
+    cu_kv = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32).cuda()
+    qd, kd, vd = dev_bf16(np.concatenate(qs)), dev_bf16(np.concatenate(ks)), dev_bf16(np.concatenate(vs))
+    out, lse = B.decode_attn(qd, kd, vd, scale, cu_q=cu_q, cu_kv=cu_kv, max_q_len=max(q_lens),
+                             max_kv_len=max(lens), want_lse=True)
+    torch.cuda.synchronize()
+    o = 0
+    for i, ql in enumerate(q_lens):
+        if ql:
+            want, want_lse = oracle.decode_attn(qs[i], ks[i], vs[i], scale)
+            assert_attn_close(out[o:o + ql], want, f"request {i} of lens {lens[:6]}...")
+            np.testing.assert_allclose(host_f64(lse[o:o + ql]), want_lse, atol=2e-3, rtol=1e-4)
+        o += ql
+
+
+@pytest.mark.parametrize("lens,q_lens,hq,hkv,d", [
+    # fewer tiles than workgroups: every workgroup holds one tile
+    ([70, 5, 129], [3, 3, 3], 8, 2, 128),
+    # a request without queries in the middle, one key only, one long request that spans many workgroups
+    ([300, 64, 1, 9000, 17], [6, 0, 1, 6, 2], 16, 2, 128),
+    # one query per request (the single-row-block launch shape, tiles of 128 keys), head size 64
+    ([513, 128, 2047, 31, 1024, 77], [1, 1, 1, 1, 1, 1], 14, 2, 64),
+    # 64 requests: the largest batch that is cut into balanced pieces
+    ([37 + 61 * i for i in range(64)], [1 + i % 3 for i in range(64)], 8, 1, 128),
+    # 65 requests: uniform splits
+    ([50 + 13 * i for i in range(65)], [2] * 65, 4, 1, 64),
+])
+def test_batches_with_library_chosen_pieces(B, lens, q_lens, hq, hkv, d):
+    _batch_case(B, lens, q_lens, hq, hkv, d, seed=9000 + len(lens))
