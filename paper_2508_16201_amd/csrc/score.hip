@@ -42,6 +42,7 @@ constexpr int kScoreBlock = 256;       // stationary vectors per workgroup
 constexpr int kScoreStages = 3;        // LDS ring depth
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
 constexpr float kLazyMargin = 8.f;     // log2 units of headroom before the running sum is rescaled
+constexpr float kSumRedo = 0x1p100f;   // a running sum at or above this (or NaN) is recomputed with maxima tracked
 
 struct ScoreParams {
     const __bf16* q;
@@ -70,6 +71,62 @@ constexpr int score_vmcnt_imm(int n)
     return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8);
 }
 
+// ---- pieces of one sub-block (16 streamed vectors x the wave's 64 stationary ones) ----
+// A fragments of sub-block `sub` of the tile at `tile` (lane (r, c) reads streamed vector sub*16 + r)
+template <int D>
+__device__ __forceinline__ void score_load_a(const unsigned char* tile, int sub, int r, int c, bf16x8 (&af)[D / 32])
+{
+    const int it = sub * 16 + r;
+    const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+        const int x = kk * 4 + c;
+        af[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + it * (D * 2) + ((x ^ swz) * 16)));
+    }
+}
+
+template <int KK>
+__device__ __forceinline__ void score_mfma(const bf16x8 (&af)[KK], const bf16x8 (&sf)[4][KK], floatx4 (&acc)[4])
+{
+    // the four accumulators take turns, so that no MFMA waits for the one issued just before it
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb)
+            acc[sb] = mfma16(af[kk], sf[sb][kk], kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[sb]);
+    }
+}
+
+// pass A, first half: mask (key0 = the lane's first key of the sub-block), maxima per row, and the
+// rare rescale of the running sums when some row's maximum outgrows its reference
+__device__ __forceinline__ void score_rows_max(floatx4 (&acc)[4], bool mask, int key0, int s_end, const int (&lim)[4],
+                                               float scale_log2, float (&m_ref)[4], float (&l_run)[4])
+{
+    float tmax[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) {
+        if (mask) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (key0 + i >= s_end || key0 + i > lim[sb]) acc[sb][i] = -INFINITY;
+        }
+        // the logits stay unscaled: the scale (>= 0) is applied to the maximum once and rides in
+        // the fused multiply-add that forms each exponent
+        tmax[sb] = fmaxf(fmaxf(acc[sb][0], acc[sb][1]), fmaxf(acc[sb][2], acc[sb][3])) * scale_log2;
+    }
+    bool grow = false;
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) grow = grow || (tmax[sb] > m_ref[sb] + kLazyMargin);
+    if (__any(grow)) {
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb) {
+            const float m_new = fmaxf(m_ref[sb], tmax[sb]);
+            l_run[sb] *= fast_exp2(m_ref[sb] - m_new);
+            m_ref[sb] = m_new;
+        }
+    }
+}
+
 template <int D, int MODE>
 __global__ __launch_bounds__(256)
 void score_sweep_kernel(const ScoreParams p)
@@ -81,8 +138,13 @@ void score_sweep_kernel(const ScoreParams p)
     constexpr int VEC_PER_LOAD = kWave / CH;         // vectors one wave-wide load covers
     constexpr int LPW = kScoreTile / VEC_PER_LOAD / 4;   // loads per wave per tile (4 waves)
     constexpr int NS = kScoreStages;
-    __shared__ __align__(16) unsigned char s_tile[NS][TILE_BYTES];
-    __shared__ __align__(16) float s_lse[NS][kScoreTile];
+    // One LDS object for everything the direct-to-LDS loads fill (the compiler orders reads of an
+    // object after ALL loads in flight into it when it sees several such objects): NS tiles, then
+    // per stage and wave a private copy of the tile's 64 row normalisers.
+    constexpr int LSE_BYTES = kScoreTile * 4;
+    __shared__ __align__(16) unsigned char s_mem[NS * TILE_BYTES + NS * 4 * LSE_BYTES];
+    unsigned char* const s_tile = s_mem;
+    unsigned char* const s_lse = s_mem + NS * TILE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -143,142 +205,192 @@ void score_sweep_kernel(const ScoreParams p)
     for (int sb = 0; sb < 4; ++sb) { m_ref[sb] = kNegBig; l_run[sb] = 0.f; col[sb] = 0.f; }
 
     // ---- loader: direct-to-LDS, load j of a wave covers VEC_PER_LOAD vectors ----
+    // The per-lane part of a load's address is the same for every tile: byte offset of the lane's
+    // vector and chunk from the tile's first vector.  A tile then costs one scalar base address;
+    // only a tile that runs past the last vector takes the per-lane clamped path.
     const int ld_vec = lane / CH, ld_chunk = lane % CH;
-    auto issue_tile = [&](int tile, int stage) {
-        const int first = s_begin + tile * kScoreTile;
-        // pass B: the tile holds consecutive text queries of one q head
-        int gl = 0, i0 = 0;
-        if (MODE == 1) { gl = first / p.l_pad; i0 = first % p.l_pad; }
+    const int64_t s_tok = (MODE == 0) ? p.k_tok : p.q_tok;       // streamed side: token stride (elements)
+    uint32_t voff[LPW];
 #pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            const int n = wave + 4 * j;                          // load index inside the tile
-            const int it = n * VEC_PER_LOAD + ld_vec;            // vector inside the tile
-            const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
-            const int chunk = ld_chunk ^ swz;
-            const __bf16* src;
-            if (MODE == 0) {
-                const int key = min(first + it, p.n_keys - 1);   // rows past the range are masked later
-                src = p.k + (int64_t)key * p.k_tok + (int64_t)g * p.k_head;
-            } else {
-                const int i = min(i0 + it, p.n_text - 1);        // padded rows carry lse = +inf
-                src = p.q + (int64_t)i * p.q_tok + (int64_t)(g * p.group + gl) * p.q_head;
-            }
-            __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(src + chunk * 8),
-                                             (SPECVLM_AS3 void*)(&s_tile[stage][n * 1024]), 16, 0, 0);
+    for (int j = 0; j < LPW; ++j) {
+        const int it = (wave + 4 * j) * VEC_PER_LOAD + ld_vec;   // vector inside the tile
+        const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+        voff[j] = (uint32_t)it * (uint32_t)(s_tok * 2) + (uint32_t)((ld_chunk ^ swz) * 16);
+    }
+    // Tiles are requested in order; the position of the next one is carried along (pass B: text
+    // query nx_idx0 of q head nx_gl) instead of being divided out of the tile index every time.
+    const int n_tiles = (s_end - s_begin + kScoreTile - 1) / kScoreTile;
+    int nx_tile = 0, nx_idx0 = s_begin, nx_gl = 0;
+    if (MODE == 1) { nx_gl = s_begin / p.l_pad; nx_idx0 = s_begin % p.l_pad; }
+    auto issue_next = [&](int stage) {
+        // pass A streams keys of kv head g; pass B streams consecutive text queries of ONE q head
+        const int idx0 = nx_idx0;
+        const int limit = (MODE == 0) ? p.n_keys : p.n_text;
+        const int64_t head_off = (MODE == 0) ? (int64_t)g * p.k_head : (int64_t)(g * p.group + nx_gl) * p.q_head;
+        const __bf16* base = (MODE == 0) ? p.k : p.q;
+        const int first = (MODE == 0) ? idx0 : nx_gl * p.l_pad + idx0;
+        if (nx_tile + 1 < n_tiles) {          // past the end the last tile is requested again
+            ++nx_tile;
+            nx_idx0 += kScoreTile;
+            if (MODE == 1 && nx_idx0 >= p.l_pad) { nx_idx0 = 0; ++nx_gl; }
         }
-        if (MODE == 1 && wave == 0) {
-            // the tile's 64 row normalisers (+inf for padded rows), one dword per lane
+        if (idx0 + kScoreTile <= limit) {
+            const char* tile_base = reinterpret_cast<const char*>(base + (int64_t)idx0 * s_tok + head_off);
+#pragma unroll
+            for (int j = 0; j < LPW; ++j)
+                __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(tile_base + voff[j]),
+                    (SPECVLM_AS3 void*)(s_tile + stage * TILE_BYTES + (wave + 4 * j) * 1024), 16, 0, 0);
+        } else {
+            // vectors past the end are masked later (pass A) or carry lse = +inf (pass B): re-read the last one
+#pragma unroll
+            for (int j = 0; j < LPW; ++j) {
+                const int n = wave + 4 * j;
+                const int it = n * VEC_PER_LOAD + ld_vec;
+                const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+                const int idx = min(idx0 + it, limit - 1);
+                const __bf16* src = base + (int64_t)idx * s_tok + head_off + (ld_chunk ^ swz) * 8;
+                __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src,
+                    (SPECVLM_AS3 void*)(s_tile + stage * TILE_BYTES + n * 1024), 16, 0, 0);
+            }
+        }
+        if (MODE == 1) {
+            // the tile's 64 row normalisers (+inf for padded rows), one dword per lane; every wave
+            // fetches its own copy, so all waves have the same number of loads in flight per tile
             const float* src = p.lse2 + (int64_t)g * p.rows_pad + first + lane;
             __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src,
-                                             (SPECVLM_AS3 void*)(&s_lse[stage][0]), 4, 0, 0);
+                                             (SPECVLM_AS3 void*)(s_lse + (stage * 4 + wave) * LSE_BYTES), 4, 0, 0);
         }
     };
 
-    auto compute = [&](int stage, int first) {
-        bool mask = false;
-        if (MODE == 0) {
-            // earliest text query among the workgroup's rows sees keys <= text_pos0
-            mask = (first + kScoreTile > s_end) || (first + kScoreTile - 1 > p.text_pos0);
+    // ---- one tile: 4 sub-blocks of 16 streamed vectors against the wave's 64 stationary ones ----
+    // Software pipeline inside the wave: while the VALU turns the logits of sub-block s into
+    // exponentials, the matrix unit already forms the logits of sub-block s+1 (independent MFMA and
+    // VALU instructions of one wave overlap), and the A fragments are read from LDS two sub-blocks
+    // ahead.  The order is written out piece by piece -- one MFMA, one logit's fma / exp / add --
+    // and pinned with scheduling barriers: left alone, the scheduler moves every chain of MFMAs
+    // next to its consumer again.  Even sub-blocks live in (af0, acc0), odd ones in (af1, acc1).
+    // (a zero scale is taken as a vanishing one, so that a masked logit, -inf, times the scale stays
+    // -inf instead of becoming NaN; every other logit still scales to 0)
+    const float sc_a = fmaxf(p.scale_log2, 1e-30f);
+    auto step = [&](floatx4 (&acc_cur)[4], floatx4 (&acc_nxt)[4], bf16x8 (&af_cur)[KK], const bf16x8 (&af_nxt)[KK],
+                    const unsigned char* tile, const unsigned char* lse_w, const int sub, const int first,
+                    const int lim0, const bool mask, const bool track, const bool has_next, const bool has_load)
+        __attribute__((always_inline)) {
+        floatx4 lse4 = {0.f, 0.f, 0.f, 0.f};
+        if (MODE == 1) lse4 = *reinterpret_cast<const floatx4*>(lse_w + (sub * 16 + 4 * c) * 4);
+        if (MODE == 0 && track)
+            score_rows_max(acc_cur, mask, first + sub * 16 + 4 * c, s_end, lim, p.scale_log2, m_ref, l_run);
+        __builtin_amdgcn_sched_barrier(0);
+        // Piece i: MFMA i of the next sub-block, the exponent of logit i, the exponential of logit
+        // i-1 and the addition of logit i-2: every input was produced a piece earlier, so the wave
+        // does not wait on the latency of its own previous instruction.
+        float part = 0.f, x_prev = 0.f, y_prev = 0.f;
+#pragma unroll
+        for (int i = 0; i < 18; ++i) {
+            if (has_next && i < 4 * KK) {
+                // neighbours in this order are independent: the four accumulators take turns
+                const int kk = i / 4, sb = i % 4;
+                acc_nxt[sb] = mfma16(af_nxt[kk], sf[sb][kk], kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc_nxt[sb]);
+            }
+            if (has_load && i < KK) {
+                const int it = (sub + 2) * 16 + r;
+                const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+                af_cur[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                    tile + it * ROW_BYTES + (((i * 4 + c) ^ swz) * 16)));
+            }
+            if (i >= 2) {                                   // add logit i-2
+                const int sb = (i - 2) / 4, e = (i - 2) % 4;
+                part = (e == 0) ? y_prev : part + y_prev;
+                if (e == 3) {
+                    if (MODE == 0) l_run[sb] += part;
+                    else col[sb] += part;
+                }
+            }
+            if (i >= 1 && i <= 16) {                        // exponential of logit i-1
+                const int sb = (i - 1) / 4, e = (i - 1) % 4;
+                y_prev = fast_exp2(x_prev);
+                // text query (lim0 + sub*16 + e) - text_pos0 of this tile sees keys <= lim0 + sub*16 + e
+                if (MODE == 1 && mask) y_prev = (key_abs[sb] > lim0 + sub * 16 + e) ? 0.f : y_prev;
+            }
+            if (i < 16) {                                   // exponent of logit i
+                const int sb = i / 4, e = i % 4;
+                x_prev = (MODE == 0) ? fmaf(acc_cur[sb][e], sc_a, -m_ref[sb])
+                                     : fmaf(acc_cur[sb][e], p.scale_log2, -lse4[e]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll 1
-        for (int sub = 0; sub < 4; ++sub) {
-            bf16x8 af[KK];
-            const int it = sub * 16 + r;
-            const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
+    };
+    // (forced inline: as a call the lambda would get every captured array through memory)
+    auto tile_body = [&](int stage, int first, int i0, bool mask, bool track) __attribute__((always_inline)) {
+        const unsigned char* tile = s_tile + stage * TILE_BYTES;
+        const unsigned char* lse_w = s_lse + (stage * 4 + wave) * LSE_BYTES;
+        const int lim0 = (MODE == 1) ? p.text_pos0 + i0 + 4 * c : 0;      // i0: the tile's first text query
+        bf16x8 af0[KK], af1[KK];
+        floatx4 acc0[4], acc1[4];
+        score_load_a<D>(tile, 0, r, c, af0);
+        score_load_a<D>(tile, 1, r, c, af1);
+        score_mfma<KK>(af0, sf, acc0);
+        step(acc0, acc1, af0, af1, tile, lse_w, 0, first, lim0, mask, track, true, true);
+        step(acc1, acc0, af1, af0, tile, lse_w, 1, first, lim0, mask, track, true, true);
+        step(acc0, acc1, af0, af1, tile, lse_w, 2, first, lim0, mask, track, true, false);
+        step(acc1, acc0, af1, af0, tile, lse_w, 3, first, lim0, mask, track, false, false);
+    };
+    auto compute = [&](int stage, int first, int i0, bool first_tile) __attribute__((always_inline)) {
+        // the mask is uniform over the tile (pass A) or the launch (pass B): copies of the
+        // straight-line body instead of branches inside it
+        if (MODE == 1) {
+            if (p.b_needs_mask) tile_body(stage, first, i0, true, false);
+            else tile_body(stage, first, i0, false, false);
+            return;
+        }
+        // earliest text query among the workgroup's rows sees keys <= text_pos0
+        const bool mask = (first + kScoreTile > s_end) || (first + kScoreTile - 1 > p.text_pos0);
+        if (mask) { tile_body(stage, first, i0, true, true); return; }
+        if (first_tile) { tile_body(stage, first, i0, false, true); return; }
+        // Pass A away from the mask: the maxima are not tracked.  The exponentials are taken
+        // against the reference the earlier tiles left; a logit far above it only makes the sum
+        // large, and a sum that is no longer a moderate finite number (overflow, or the
+        // reference still unset) sends the wave back over the same tile with tracking on.
+        float l_save[4], m_save[4];
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const int x = kk * 4 + c;
-                af[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                    &s_tile[stage][it * ROW_BYTES + ((x ^ swz) * 16)]));
-            }
-            floatx4 acc[4];
+        for (int sb = 0; sb < 4; ++sb) { l_save[sb] = l_run[sb]; m_save[sb] = m_ref[sb]; }
+        tile_body(stage, first, i0, false, false);
+        bool redo = false;
 #pragma unroll
-            for (int sb = 0; sb < 4; ++sb) {
-                acc[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int sb = 0; sb < 4; ++sb) redo = redo || !(l_run[sb] < kSumRedo);
+        if (__any(redo)) {
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) acc[sb] = mfma16(af[kk], sf[sb][kk], acc[sb]);
-            }
-            if (MODE == 0) {
-                // (a zero scale is taken as a vanishing one, so that a masked logit, -inf, times the
-                // scale stays -inf instead of becoming NaN; every other logit still scales to 0)
-                const float sc_a = fmaxf(p.scale_log2, 1e-30f);
-                float tmax[4];
-#pragma unroll
-                for (int sb = 0; sb < 4; ++sb) {
-                    if (mask) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int key = first + sub * 16 + 4 * c + i;
-                            if (key >= s_end || key > lim[sb]) acc[sb][i] = -INFINITY;
-                        }
-                    }
-                    // the logits stay unscaled: the scale (>= 0) is applied to the maximum once and
-                    // rides in the fused multiply-add that forms each exponent
-                    tmax[sb] = fmaxf(fmaxf(acc[sb][0], acc[sb][1]), fmaxf(acc[sb][2], acc[sb][3])) * p.scale_log2;
-                }
-                // rescale only when some row's new maximum outgrows its reference
-                bool grow = false;
-#pragma unroll
-                for (int sb = 0; sb < 4; ++sb) grow = grow || (tmax[sb] > m_ref[sb] + kLazyMargin);
-                if (__any(grow)) {
-#pragma unroll
-                    for (int sb = 0; sb < 4; ++sb) {
-                        const float m_new = fmaxf(m_ref[sb], tmax[sb]);
-                        l_run[sb] *= fast_exp2(m_ref[sb] - m_new);
-                        m_ref[sb] = m_new;
-                    }
-                }
-#pragma unroll
-                for (int sb = 0; sb < 4; ++sb) {
-                    const float sc = sc_a, mr = m_ref[sb];
-                    const float sum = (fast_exp2(fmaf(acc[sb][0], sc, -mr)) + fast_exp2(fmaf(acc[sb][1], sc, -mr))) +
-                                      (fast_exp2(fmaf(acc[sb][2], sc, -mr)) + fast_exp2(fmaf(acc[sb][3], sc, -mr)));
-                    l_run[sb] += sum;
-                }
-            } else {
-                const floatx4 lse4 = *reinterpret_cast<const floatx4*>(&s_lse[stage][sub * 16 + 4 * c]);
-                if (p.b_needs_mask) {
-                    // text query i of this tile sees keys <= text_pos0 + i
-                    const int lim0 = p.text_pos0 + (first % p.l_pad) + sub * 16 + 4 * c;
-#pragma unroll
-                    for (int sb = 0; sb < 4; ++sb) {
-                        float sum = 0.f;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float pr = fast_exp2(acc[sb][i] * p.scale_log2 - lse4[i]);
-                            sum += (key_abs[sb] > lim0 + i) ? 0.f : pr;
-                        }
-                        col[sb] += sum;
-                    }
-                } else {
-#pragma unroll
-                    for (int sb = 0; sb < 4; ++sb) {
-                        const float sum = (fast_exp2(acc[sb][0] * p.scale_log2 - lse4[0]) +
-                                           fast_exp2(acc[sb][1] * p.scale_log2 - lse4[1])) +
-                                          (fast_exp2(acc[sb][2] * p.scale_log2 - lse4[2]) +
-                                           fast_exp2(acc[sb][3] * p.scale_log2 - lse4[3]));
-                        col[sb] += sum;
-                    }
-                }
-            }
+            for (int sb = 0; sb < 4; ++sb) { l_run[sb] = l_save[sb]; m_ref[sb] = m_save[sb]; }
+            tile_body(stage, first, i0, false, true);
         }
     };
 
     // ---- ring: NS-1 tiles in flight while one is consumed; one barrier per tile ----
-    const int n_tiles = (s_end - s_begin + kScoreTile - 1) / kScoreTile;
+    // Every wave issues the same number of loads for every tile, in straight-line code: the
+    // prologue always fills NS-1 stages and every iteration issues one more tile (past the end of
+    // the range the last tile is fetched again into a stage nobody reads), so "tile t has landed"
+    // is the constant wait vmcnt <= (NS-2) tiles' worth and nothing makes the compiler add a
+    // full drain inside the loop.
+    constexpr int LPT = LPW + (MODE == 1 ? 1 : 0);       // loads per wave per tile
+    if (n_tiles > 0) {
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < n_tiles) issue_tile(s, s);
-    for (int t = 0; t < n_tiles; ++t) {
-        const int younger = min(NS - 2, n_tiles - 1 - t);
-        // (wave 0 of pass B has one more load per tile: it waits slightly longer than needed)
-        if (younger >= 1) __builtin_amdgcn_s_waitcnt(score_vmcnt_imm(LPW) & ~(15 << 8));
-        else __builtin_amdgcn_s_waitcnt(score_vmcnt_imm(0) & ~(15 << 8));
-        __asm__ volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        __asm__ volatile("" ::: "memory");
-        if (t + NS - 1 < n_tiles) issue_tile(t + NS - 1, (t + NS - 1) % NS);
-        compute(t % NS, s_begin + t * kScoreTile);
+        for (int s = 0; s < NS - 1; ++s) issue_next(s);
+        // the stationary fragments (older than the tiles just requested) are in their registers
+        __builtin_amdgcn_s_waitcnt(score_vmcnt_imm((NS - 1) * LPT) & ~(15 << 8));
+        int t = 0, st_use = 0, st_fill = NS - 1;         // stage consumed / stage refilled this iteration
+        int use_i0 = (MODE == 1) ? s_begin % p.l_pad : 0;   // pass B: first text query of the tile consumed
+        do {
+            __builtin_amdgcn_s_waitcnt(score_vmcnt_imm((NS - 2) * LPT) & ~(15 << 8));
+            __asm__ volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            __asm__ volatile("" ::: "memory");
+            issue_next(st_fill);
+            compute(st_use, s_begin + t * kScoreTile, use_i0, t == 0);
+            if (MODE == 1) { use_i0 += kScoreTile; if (use_i0 >= p.l_pad) use_i0 = 0; }
+            st_use = (st_use + 1 == NS) ? 0 : st_use + 1;
+            st_fill = (st_fill + 1 == NS) ? 0 : st_fill + 1;
+        } while (++t < n_tiles);
+        __builtin_amdgcn_s_waitcnt(score_vmcnt_imm(0) & ~(15 << 8));   // the surplus loads land before the workgroup ends
     }
 
     // ---- reduce over the four lane groups that share a stationary vector ----
@@ -350,7 +462,7 @@ struct ScorePlan {
 };
 
 static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video, int n_q_heads,
-                            int n_kv_heads, int norm_mode, int have_row_lse)
+                            int n_kv_heads, int head_dim, int norm_mode, int have_row_lse)
 {
     ScorePlan s;
     const int group = n_q_heads / n_kv_heads;
@@ -360,10 +472,11 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
     s.video_pad = round_up(n_video > 0 ? n_video : 1, kScoreBlock);
     s.key_lo = norm_mode ? video_start : 0;
     s.key_hi = norm_mode ? video_start + n_video : n_keys;
-    // Three workgroups fit a CU (48 KB of LDS ring, < 170 VGPRs).  A split count is
+    // Workgroups resident per CU: two at head size 128 (about 190 VGPRs with the software
+    // pipeline's second set of fragments and accumulators), three at 64.  A split count is
     // good when the workgroups fill whole rounds of those slots: minimise
     // rounds x tiles-per-workgroup, ties to the fewer splits (less partial traffic).
-    const int slots = 3 * kNumCu;
+    const int slots = (head_dim == 128 ? 2 : 3) * kNumCu;
     auto best_splits = [&](int blocks, int streamed, int max_splits, int* per_split) {
         int best = 1, best_per = round_up(streamed > 0 ? streamed : 1, kScoreTile);
         long best_cost = -1;
@@ -402,13 +515,12 @@ extern "C" size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_key
                                                 int n_q_heads, int n_kv_heads, int head_dim,
                                                 int have_row_lse)
 {
-    (void)head_dim;
     if (batch != 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
         n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
         return 0;
     // the split plan depends on the normalisation domain; size for the larger one
-    const ScorePlan a = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, 0, have_row_lse);
-    const ScorePlan b = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, 1, have_row_lse);
+    const ScorePlan a = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
+    const ScorePlan b = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
     return a.total > b.total ? a.total : b.total;
 }
 
@@ -434,9 +546,12 @@ extern "C" int specvlm_score(
     if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
     if ((q_tok_stride | q_head_stride | k_tok_stride | k_head_stride) & 7) return SPECVLM_EUNSUPPORTED;
     if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
+    // a lane's byte offset inside a 64-vector tile is kept in 32 bits
+    if (q_tok_stride < 0 || k_tok_stride < 0 || q_tok_stride >= (1 << 24) || k_tok_stride >= (1 << 24))
+        return SPECVLM_EUNSUPPORTED;
 
     const ScorePlan plan = score_plan(n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
-                                      norm_mode, row_lse != nullptr);
+                                      head_dim, norm_mode, row_lse != nullptr);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.total) return SPECVLM_EWORKSPACE;
 
     ScoreParams p;

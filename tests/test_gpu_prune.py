@@ -76,6 +76,27 @@ def test_score_zero_scale_is_the_closed_form(B):
     np.testing.assert_allclose(host_f64(got), np.full(V, 1.0 / V), rtol=1e-5)
 
 
+@pytest.mark.parametrize("d,hq,hkv", [(128, 8, 2), (64, 4, 1)])
+def test_score_logits_that_outgrow_the_earlier_tiles(B, d, hq, hkv):
+    """Keys whose logits exceed everything seen in the earlier tiles by far more than fp32's
+    exponent range: the row statistics must come out as if the maximum had been known up front
+    (small keys first, then keys 32x larger, then small ones again)."""
+    V, L = 2200, 70
+    q = rnd_bits((L, hq, d), 170)
+    kf = np.random.default_rng(171).standard_normal((V + L, hkv, d)).astype(np.float32)
+    kf[:700] *= 0.25
+    kf[700:1500] *= 32.0
+    kf[1500:] *= 0.5
+    k = synth.f32_to_bf16_bits(kf)
+    scale = 1.0 / np.sqrt(d)
+    for mode in (0, 1):
+        want = oracle.score(q, k, 0, V, V, scale, norm_mode=mode)
+        got = B.score(dev_bf16(q), dev_bf16(k), 0, V, V, scale, norm_mode=mode)
+        torch.cuda.synchronize()
+        assert np.isfinite(host_f64(got)).all()
+        assert_scores_close(got, want, f"outgrowing logits d{d} mode{mode}")
+
+
 def test_score_text_queries_inside_video_span_are_causal(B):
     V, L, hq, hkv, d = 300, 40, 4, 2, 64
     q, k = rnd_bits((L, hq, d), 60), rnd_bits((V + L, hkv, d), 61)
