@@ -299,10 +299,13 @@ int specvlm_accept_tree(
  *   FRAME_DROP     F_k = floor(B / (grid_h*grid_w)) whole frames, frames floor(t*F/F_k)
  *   LATTICE        in every frame the rows that are multiples of stride_h and the
  *                  columns that are multiples of stride_w (B unused)
+ *   UNIFORM_PER_FRAME  the uniform stride restarted in every frame: frame f owns the
+ *                  output positions floor(f*B/F) .. floor((f+1)*B/F) - 1 (B_f of them)
+ *                  and keeps its tokens floor(u*grid_h*grid_w/B_f), u = 0..B_f-1
  *   RANDOM         token j draws the 30 high bits of output j of the SplitMix64
  *                  stream seeded with `seed`; the B largest draws are kept, equal
  *                  draws by lower index (V <= 65536)
- * FRAME_DROP and LATTICE need n_frames*grid_h*grid_w == V; the other modes
+ * FRAME_DROP, LATTICE and UNIFORM_PER_FRAME need n_frames*grid_h*grid_w == V; the other modes
  * ignore the grid arguments.  specvlm_baseline_count (host arithmetic only)
  * returns how many indices the mode writes, or a negative status;
  * keep_idx (device int32, that many entries) receives them in ascending order.
@@ -315,6 +318,7 @@ int specvlm_accept_tree(
 #define SPECVLM_BASELINE_FRAME_DROP    4
 #define SPECVLM_BASELINE_LATTICE       5
 #define SPECVLM_BASELINE_RANDOM        6
+#define SPECVLM_BASELINE_UNIFORM_PER_FRAME 7
 
 int specvlm_baseline_count(int mode, int n_video, int n_frames, int grid_h, int grid_w,
                            int keep_budget, int stride_h, int stride_w);

@@ -190,7 +190,7 @@ def accept_tree_greedy(target_logits, node_tokens, parent) -> Tuple[int, np.ndar
 
 
 BASELINE_MODES = {"window-front": 0, "window-middle": 1, "window-end": 2, "uniform": 3,
-                  "frame-drop": 4, "lattice": 5, "random": 6}
+                  "frame-drop": 4, "lattice": 5, "random": 6, "uniform-per-frame": 7}
 
 
 def splitmix64(seed: int, j: int) -> int:

@@ -537,7 +537,7 @@ int oracle_baseline_keep(int mode, int n_video, int n_frames, int grid_h, int gr
     const int64_t V = n_video, B = keep_budget;
     if (V < 0 || B < 0 || B > V) return -1;
     const int64_t tpf = (int64_t)grid_h * grid_w;
-    if (mode == 4 || mode == 5) {
+    if (mode == 4 || mode == 5 || mode == 7) {
         if (n_frames < 0 || grid_h <= 0 || grid_w <= 0 || tpf * n_frames != V) return -1;
     }
     int n = 0;
@@ -574,6 +574,16 @@ int oracle_baseline_keep(int mode, int n_video, int n_frames, int grid_h, int gr
         free(order);
         break;
     }
+    case 7:
+        /* Eq. 7 with an empty V_R, restarted in every frame: the budget is dealt to the frames in
+         * order (frame f gets the output positions floor(f*B/F) .. floor((f+1)*B/F) - 1) and each
+         * frame strides its own grid from its first token. */
+        for (int64_t f = 0; f < n_frames; ++f) {
+            const int64_t lo = (f * B) / n_frames, hi = ((f + 1) * B) / n_frames;
+            for (int64_t u = 0; u < hi - lo; ++u)
+                keep_idx[n++] = (int32_t)(f * tpf + (u * tpf) / (hi - lo));
+        }
+        break;
     default: return -1;
     }
     return n;

@@ -327,7 +327,7 @@ def accept_tree(target_logits: torch.Tensor, node_tokens: torch.Tensor, parent: 
 
 # ------------------------------------------------------------------- baseline pruners
 BASELINE_MODES = {"window-front": 0, "window-middle": 1, "window-end": 2, "uniform": 3,
-                  "frame-drop": 4, "lattice": 5, "random": 6}
+                  "frame-drop": 4, "lattice": 5, "random": 6, "uniform-per-frame": 7}
 
 
 def baseline_keep(mode: str, n_video: int, keep_budget: int, *, n_frames: int = 0, grid_h: int = 0,

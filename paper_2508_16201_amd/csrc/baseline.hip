@@ -1,6 +1,7 @@
 // specvlm_baseline_keep: retention sets of the attention-agnostic pruners the
 // paper's ablations run against SpecVLM (Sec. 2.2: random pruning; Sec. 5.2:
-// windows over the front, middle and end of the video; SD-Uniform; SD-Frame).
+// windows over the front, middle and end of the video; SD-Uniform, also restarted
+// per frame or as a 2-D lattice; SD-Frame).
 // Every mode except the random one is a closed form of the output position, so
 // one thread writes one index.  The random mode draws one SplitMix64 output
 // per token (counter-based: output j of the stream depends on (seed, j) only),
@@ -41,6 +42,14 @@ void baseline_index_kernel(const BaselineParams p)
         const int cw = (p.grid_w + p.stride_w - 1) / p.stride_w;
         const int f = t / (ch * cw), rem = t % (ch * cw);
         idx = (int64_t)f * tpf + (int64_t)(rem / cw) * p.stride_h * p.grid_w + (rem % cw) * p.stride_w;
+        break;
+    }
+    case SPECVLM_BASELINE_UNIFORM_PER_FRAME: {
+        // output position t belongs to the frame f with floor(f*B/F) <= t < floor((f+1)*B/F)
+        const int64_t F = p.n_frames;
+        const int64_t f = ((int64_t)(t + 1) * F - 1) / B;
+        const int64_t lo = (f * B) / F, hi = ((f + 1) * B) / F;
+        idx = f * tpf + ((t - lo) * tpf) / (hi - lo);
         break;
     }
     default: break;
@@ -84,10 +93,12 @@ extern "C" int specvlm_baseline_count(int mode, int n_video, int n_frames, int g
     case SPECVLM_BASELINE_RANDOM:
         return n_video > 65536 ? SPECVLM_EUNSUPPORTED : keep_budget;
     case SPECVLM_BASELINE_FRAME_DROP:
-    case SPECVLM_BASELINE_LATTICE: {
+    case SPECVLM_BASELINE_LATTICE:
+    case SPECVLM_BASELINE_UNIFORM_PER_FRAME: {
         if (n_frames < 0 || grid_h <= 0 || grid_w <= 0) return SPECVLM_EINVAL;
         const int64_t tpf = (int64_t)grid_h * grid_w;
         if (tpf * n_frames != n_video) return SPECVLM_EINVAL;
+        if (mode == SPECVLM_BASELINE_UNIFORM_PER_FRAME) return keep_budget;
         if (mode == SPECVLM_BASELINE_FRAME_DROP) return (int)((keep_budget / tpf) * tpf);
         if (stride_h <= 0 || stride_w <= 0) return SPECVLM_EINVAL;
         return n_frames * ((grid_h + stride_h - 1) / stride_h) * ((grid_w + stride_w - 1) / stride_w);

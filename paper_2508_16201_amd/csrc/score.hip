@@ -473,10 +473,12 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
     s.key_lo = norm_mode ? video_start : 0;
     s.key_hi = norm_mode ? video_start + n_video : n_keys;
     // Workgroups resident per CU: two at head size 128 (about 190 VGPRs with the software
-    // pipeline's second set of fragments and accumulators), three at 64.  A split count is
-    // good when the workgroups fill whole rounds of those slots: minimise
-    // rounds x tiles-per-workgroup, ties to the fewer splits (less partial traffic).
-    const int slots = (head_dim == 128 ? 2 : 3) * kNumCu;
+    // pipeline's second set of fragments and accumulators), three at 64.  The dispatcher hands a
+    // CU its next workgroup as soon as one ends, so a CU that is dealt w workgroups works through
+    // them `resident` at a time: its time is about max(w, resident) / resident workgroup
+    // lifetimes (below `resident` the CU is under-used, not faster).  Minimise that, ties to the
+    // fewer splits (less partial traffic).
+    const int resident = head_dim == 128 ? 2 : 3;
     auto best_splits = [&](int blocks, int streamed, int max_splits, int* per_split) {
         int best = 1, best_per = round_up(streamed > 0 ? streamed : 1, kScoreTile);
         long best_cost = -1;
@@ -485,9 +487,9 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
             const int live = streamed > 0 ? (streamed + per - 1) / per : 1;
             if (live != n) continue;                             // same partition as a smaller n
             const long wgs = (long)blocks * live;
-            const long rounds = (wgs + slots - 1) / slots;
+            const long per_cu = (wgs + kNumCu - 1) / kNumCu;
             // +2 tiles: a workgroup's fixed cost (stationary fragments, ring fill); + live: fewer splits on ties
-            const long cost = rounds * (per / kScoreTile + 2) * 64 + live;
+            const long cost = (per_cu > resident ? per_cu : resident) * (per / kScoreTile + 2) * 64 / resident + live;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = live; best_per = per; }
         }
         *per_split = best_per;

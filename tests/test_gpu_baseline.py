@@ -45,6 +45,15 @@ def test_lattice(B, F, gh, gw, sh, sw):
     assert np.array_equal(got, oracle.baseline_keep("lattice", V, 0, **kw))
 
 
+@pytest.mark.parametrize("F,gh,gw,Bud", [(64, 14, 14, 1254), (128, 16, 16, 3277), (8, 14, 14, 1), (8, 14, 14, 7),
+                                         (8, 14, 14, 1568), (3, 2, 3, 4), (1, 5, 7, 11), (64, 14, 14, 0)])
+def test_uniform_per_frame(B, F, gh, gw, Bud):
+    V = F * gh * gw
+    kw = dict(n_frames=F, grid_h=gh, grid_w=gw)
+    got = host(B.baseline_keep("uniform-per-frame", V, Bud, **kw))
+    assert np.array_equal(got, oracle.baseline_keep("uniform-per-frame", V, Bud, **kw))
+
+
 @pytest.mark.parametrize("V,Bud,seed", [(1568, 157, 0), (12544, 1254, 1), (25088, 2509, 2), (65536, 6554, 3),
                                         (3000, 1500, 2**63 + 11), (97, 41, 5), (64, 64, 6), (1025, 1, 7),
                                         (40000, 39999, 8)])

@@ -80,6 +80,30 @@ def _splitmix_py(seed, j):
     return z ^ (z >> 31)
 
 
+def test_uniform_per_frame_pins():
+    """Restarted stride: (a) when B is a multiple of F every frame holds the flat stride of its own
+    grid, shifted; (b) frame shares differ by at most one and add up to B; (c) every frame with a
+    share keeps its first token; (d) a full budget keeps everything; (e) a hand-worked case."""
+    F, gh, gw = 8, 14, 14
+    tpf, V = gh * gw, F * gh * gw
+    got = oracle.baseline_keep("uniform-per-frame", V, 8 * 20, n_frames=F, grid_h=gh, grid_w=gw)
+    per = np.array([(u * tpf) // 20 for u in range(20)])
+    assert np.array_equal(got, np.concatenate([f * tpf + per for f in range(F)]))
+    for Bud in (157, 1, 7, 9, 1567):
+        got = oracle.baseline_keep("uniform-per-frame", V, Bud, n_frames=F, grid_h=gh, grid_w=gw)
+        assert len(got) == Bud and np.all(np.diff(got) > 0)
+        share = np.bincount(got // tpf, minlength=F)
+        assert share.max() - share.min() <= 1 and share.sum() == Bud
+        for f in range(F):
+            if share[f]:
+                assert got[got // tpf == f][0] == f * tpf
+    assert np.array_equal(oracle.baseline_keep("uniform-per-frame", V, V, n_frames=F, grid_h=gh, grid_w=gw),
+                          np.arange(V))
+    # 3 frames of 2x3 tokens, budget 4: shares 1, 1, 2 (positions floor(f*4/3)); the last frame keeps 0 and 3
+    got = oracle.baseline_keep("uniform-per-frame", 18, 4, n_frames=3, grid_h=2, grid_w=3)
+    assert got.tolist() == [0, 6, 12, 15]
+
+
 def test_random_is_the_top_draws_of_the_stream():
     V, B, seed = 3000, 300, 99
     draws = np.array([_splitmix_py(seed, j) >> 34 for j in range(V)], dtype=np.int64)
