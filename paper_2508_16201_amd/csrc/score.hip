@@ -433,11 +433,21 @@ void score_lse_kernel(const ScoreParams p)
             out = p.row_lse[(int64_t)i * p.n_q_heads + g * p.group + gl] * kLog2e;
             if (!(out > -INFINITY)) out = INFINITY;
         } else {
-            const float* src = p.part_ml + ((int64_t)g * p.rows_pad + row) * p.a_splits * 2;
-            float m = kNegBig;
-            for (int s = 0; s < p.a_splits; ++s) m = fmaxf(m, src[2 * s]);
-            float l = 0.f;
-            for (int s = 0; s < p.a_splits; ++s) l += src[2 * s + 1] * fast_exp2(src[2 * s] - m);
+            const float2* src = reinterpret_cast<const float2*>(p.part_ml) + ((int64_t)g * p.rows_pad + row) * p.a_splits;
+            // online merge of the (max, sum) pairs, eight loads in flight at a time
+            float m = kNegBig, l = 0.f;
+            for (int s0 = 0; s0 < p.a_splits; s0 += 8) {
+                float2 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = (s0 + u < p.a_splits) ? src[s0 + u] : float2{kNegBig, 0.f};
+                float mc = m;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) mc = fmaxf(mc, v[u].x);
+                l *= fast_exp2(m - mc);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) l += v[u].y * fast_exp2(v[u].x - mc);
+                m = mc;
+            }
             if (l > 0.f) out = m + fast_log2(l);
         }
     }
@@ -451,7 +461,15 @@ void score_final_kernel(const ScoreParams p)
     if (j >= p.n_video) return;
     float a = 0.f;
     const int parts = p.n_kv_heads * p.b_splits;
-    for (int s = 0; s < parts; ++s) a += p.part_cols[(int64_t)s * p.video_pad + j];
+    // eight loads in flight at a time; the additions keep the order s = 0, 1, 2, ...
+    for (int s0 = 0; s0 < parts; s0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = (s0 + u < parts) ? p.part_cols[(int64_t)(s0 + u) * p.video_pad + j] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
     a *= p.inv_count;
     p.scores[j] = (p.beta != 0.f ? p.beta * p.scores[j] : 0.f) + a;
 }
