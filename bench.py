@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 # HBM bytes per verify-attention launch (split + merge) from the rocprofv3 PMC runs summarised in
 # profiles/bench_72b-full_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE, scaled by the copy-kernel factors).
 # Only valid for the default launch shape of that workload.
-MEASURED_TRAFFIC_BYTES = {("72b-full", "head-major", 0): 62.13e6}
+MEASURED_TRAFFIC_BYTES = {("72b-full", "head-major", 0): 62.18e6}
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
