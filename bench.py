@@ -41,7 +41,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="72b-full")
-    ap.add_argument("--layout", default="head-major", choices=["head-major", "token-major"])
+    ap.add_argument("--layout", default=None, choices=["head-major", "token-major"],
+                    help="KV layout; default head-major ([H_kv][tokens][d], for a batch over the packed token axis)")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sampling", action="store_true", help="rejection-sampling accept instead of greedy")
@@ -70,6 +71,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.attn_only:
         return attn_only(args, torch, B, synth)
+    if args.layout is None:
+        args.layout = "head-major"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = synth.WORKLOADS[args.workload]
@@ -354,9 +357,11 @@ def attn_only(args, torch, B, synth):
     def randn_bf16(shape):
         return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
 
-    # request-major, then head-major inside a request: [request][H_kv][kv_len_b][d], addressed as one
-    # [sum kv_len, H_kv, d] view needs a common head stride, so ragged batches use the token-major layout
-    if batch == 1 and args.layout == "head-major":
+    # head-major: [H_kv][sum kv_len][d] (the requests packed along the token axis), viewed as
+    # [sum kv_len, H_kv, d]; token-major: [sum kv_len][H_kv][d]
+    if args.layout is None:
+        args.layout = "head-major"
+    if args.layout == "head-major":
         k = [randn_bf16((hkv, total, d)).permute(1, 0, 2) for _ in range(layers)]
         v = [randn_bf16((hkv, total, d)).permute(1, 0, 2) for _ in range(layers)]
     else:
@@ -396,7 +401,7 @@ def attn_only(args, torch, B, synth):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name} (verify attention only): batch {batch}, {total} keys, {hq}/{hkv} heads "
                                f"d{d}, gamma {w.gamma}, {layers} distinct layers",
-                   "kv_layout": args.layout if batch == 1 else "token-major",
+                   "kv_layout": args.layout,
                    "num_splits": args.num_splits},
         "verify_attn_us_per_layer": round(us, 2),
         "roofline": {"kernel": "specvlm_decode_attn (verify, split + merge)", "bound": "hbm",

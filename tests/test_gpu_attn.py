@@ -247,6 +247,8 @@ def _batch_case(B, lens, q_lens, hq, hkv, d, seed, scale=0.09):
     ([513, 128, 2047, 31, 1024, 77], [1, 1, 1, 1, 1, 1], 14, 2, 64),
     # 64 requests: the largest batch that is cut into balanced pieces
     ([37 + 61 * i for i in range(64)], [1 + i % 3 for i in range(64)], 8, 1, 128),
+    # the draft of the ragged configuration: 8 requests, one query each, 28/4 heads d 128, pruned caches
+    ([int(f * 19.6) + 256 + 1 for f in (21, 63, 88, 101, 124, 133, 156, 167)], [1] * 8, 28, 4, 128),
     # 65 requests: uniform splits
     ([50 + 13 * i for i in range(65)], [2] * 65, 4, 1, 64),
 ])
