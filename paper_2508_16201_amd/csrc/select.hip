@@ -39,28 +39,25 @@ __device__ __forceinline__ uint32_t score_key(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Exclusive prefix sum of one int per thread over the block (thread order).
-__device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int* total)
+// Exclusive prefix sums of two ints per thread in one round of barriers.
+__device__ __forceinline__ void block_excl_scan2(int a, int b, int (*s_wave2)[kSelWaves], int* a_before, int* b_before)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int incl = v;
+    int ia = a, ib = b;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(incl, off);
-        if (lane >= off) incl += y;
+        const int ya = __shfl_up(ia, off), yb = __shfl_up(ib, off);
+        if (lane >= off) { ia += ya; ib += yb; }
     }
-    __syncthreads();                       // s_wave may still be read from a previous scan
-    if (lane == 63) s_wave[wave] = incl;
+    if (lane == 63) { s_wave2[0][wave] = ia; s_wave2[1][wave] = ib; }
     __syncthreads();
-    int before = 0, sum = 0;
+    int wa = 0, wb = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
-        const int x = s_wave[w];
-        if (w < wave) before += x;
-        sum += x;
+        if (w < wave) { wa += s_wave2[0][w]; wb += s_wave2[1][w]; }
     }
-    *total = sum;
-    return before + incl - v;
+    *a_before = wa + ia - a;
+    *b_before = wb + ib - b;
 }
 
 template <int E>
@@ -69,7 +66,7 @@ void select_kernel(const SelectParams p)
 {
     __shared__ int s_hist[kSelWaves][256];
     __shared__ int s_tot[256];
-    __shared__ int s_wave[kSelWaves];
+    __shared__ int s_wave2[2][kSelWaves];
     __shared__ int s_pick[2];
 
     const int b = blockIdx.x;
@@ -178,10 +175,16 @@ void select_kernel(const SelectParams p)
             else if (key[e] == prefix) eq |= 1ull << e;
         }
     }
-    int total;
-    const int eq_before = block_excl_scan(__popcll(eq), s_wave, &total);
+    // One block scan gives every thread the numbers of larger and of equal keys before its
+    // tokens; everything else that is "before me" follows in closed form: the tokens before mine
+    // are min(first, n), those taken by Stage I are the larger ones plus the equal ones up to
+    // `need`, the rest is my first remainder rank, and the stride picks below that rank are counted
+    // by the stride formula itself.
+    int gt_before, eq_before;
+    block_excl_scan2(__popcll(gt), __popcll(eq), s_wave2, &gt_before, &eq_before);
     int take = need - eq_before;
     take = take < 0 ? 0 : take;
+    const int top_before = gt_before + (eq_before < need ? eq_before : need);
     uint64_t top = gt;
     for (uint64_t m = eq; m && take > 0; --take) {
         const uint64_t bit = m & (~m + 1);
@@ -191,12 +194,14 @@ void select_kernel(const SelectParams p)
 
     // ---- Stage II: uniform stride over the remainder ----
     const uint64_t rem_mask = valid & ~top;
-    const int rho_before = block_excl_scan(__popcll(rem_mask), s_wave, &total);
+    const int rho_before = (first < n ? first : n) - top_before;
     const uint64_t R = (uint64_t)(n - k), U = (uint64_t)(budget - k);
     uint64_t uni = 0;
-    if (U > 0 && rem_mask) {
+    int uni_before = 0;                                           // stride picks with a rank below mine
+    if (U > 0) {
         uint64_t t = ((uint64_t)rho_before * U + R - 1) / R;      // first stride index at or after my ranks
-        if (t < U) {
+        uni_before = (int)(t < U ? t : U);
+        if (t < U && rem_mask) {
             uint64_t q = (t * R) / U, frac = (t * R) % U;         // rank floor(t*R/U)
             const uint64_t step_q = R / U, step_f = R % U;
             uint64_t rho = (uint64_t)rho_before;
@@ -212,9 +217,9 @@ void select_kernel(const SelectParams p)
         }
     }
 
-    // ---- stable compaction of V_R u V_U ----
+    // ---- stable compaction of V_R u V_U: my first output position is what was kept before me ----
     const uint64_t keep = top | uni;
-    int pos = out0 + block_excl_scan(__popcll(keep), s_wave, &total);
+    int pos = out0 + top_before + uni_before;
     for (uint64_t m = keep; m;) {
         const int e = __ffsll((long long)m) - 1;
         m &= m - 1;
