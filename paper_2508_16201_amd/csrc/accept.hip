@@ -5,9 +5,12 @@
 // Pass 1 (many workgroups): per (request, row, vocab chunk) partial statistics
 //   -- argmax with lowest-index ties for greedy; running (max, sum exp) of
 //   logit/T for the target rows and the draft rows for sampling.
-// Pass 2 (one workgroup per request): merge the partials, walk the gamma
-//   accept tests in order, then draw the final token by inverse CDF over the
-//   residual max(p - q, 0) (or over p when every draft survived).
+// Pass 2, greedy (one wave per request): merge the partials and walk the gamma tests in order.
+// Pass 2, sampling (many workgroups): every workgroup merges the partials and repeats the gamma
+//   accept tests (a few loads), so all agree on the first rejected position n; each then sums the
+//   mass of the residual max(p - q, 0) at row n (of p when every draft survived) over its chunk.
+// Pass 3, sampling (one workgroup per request): inverse CDF over the chunk masses, then inside
+//   the owning chunk over its waves, then inside the owning wave's tokens.
 #include "common.h"
 
 namespace specvlm {
@@ -28,6 +31,9 @@ struct AcceptParams {
     int32_t* out_tokens;
     float* part_val;          // [batch][rows][n_chunks]   max
     float* part_aux;          // [batch][rows][n_chunks]   sum exp (sampling) / argmax index bits (greedy)
+    float* norm;              // sampling: [batch][rows][2] merged (max, sum exp) of every row
+    float* chunk_mass;        // sampling: [batch][n_chunks] residual (or target) mass of row n per chunk
+    int32_t* n_rej;           // sampling: [batch] first rejected position n (gamma if none)
 };
 
 __device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i)
@@ -139,82 +145,139 @@ void accept_softmax_partial(const AcceptParams p)
     }
 }
 
-__global__ __launch_bounds__(kAccThreads)
-void accept_sample_final(const AcceptParams p)
+// Merged (max, sum exp) of every row from the pass-1 partials, into LDS.
+__device__ __forceinline__ void accept_merge_rows(const AcceptParams& p, int b, int rows, float* s_m, float* s_z)
 {
-    __shared__ float s_m[129], s_z[129];        // merged (max, sum) of up to 2*gamma+1 rows
-    __shared__ float s_w[kAccWaves], s_w2[kAccWaves];
-    __shared__ int s_idx[kAccWaves];
-    __shared__ int s_n, s_y;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rows = 2 * p.gamma + 1;
-    for (int row = tid; row < rows; row += kAccThreads) {
+    for (int row = threadIdx.x; row < rows; row += blockDim.x) {
         const int64_t slot = ((int64_t)b * rows + row) * p.n_chunks;
-        float m = -INFINITY;
-        for (int c = 0; c < p.n_chunks; ++c) m = fmaxf(m, p.part_val[slot + c]);
-        float z = 0.f;
-        for (int c = 0; c < p.n_chunks; ++c) z += p.part_aux[slot + c] * fast_exp2(p.part_val[slot + c] - m);
+        float m = -INFINITY, z = 0.f;
+        for (int c0 = 0; c0 < p.n_chunks; c0 += 8) {         // eight chunks' loads in flight at a time
+            float pm[8], pz[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool in = c0 + j < p.n_chunks;
+                pm[j] = in ? p.part_val[slot + c0 + j] : -INFINITY;
+                pz[j] = in ? p.part_aux[slot + c0 + j] : 0.f;
+            }
+            float mc = m;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) mc = fmaxf(mc, pm[j]);
+            z *= (mc == -INFINITY) ? 0.f : fast_exp2(m - mc);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) z += (pz[j] > 0.f) ? pz[j] * fast_exp2(pm[j] - mc) : 0.f;
+            m = mc;
+        }
         s_m[row] = m; s_z[row] = z;
     }
+}
+
+// weight of token v at the first rejected position: residual max(p - q, 0), or p when nothing was rejected
+struct AcceptWeight {
+    const float* trow;
+    const float* drow;        // null: no residual
+    float inv_t_log2, mt, inv_zt, md, inv_zd;
+    __device__ __forceinline__ float operator()(int v) const
+    {
+        const float pv = fast_exp2(trow[v] * inv_t_log2 - mt) * inv_zt;
+        if (!drow) return pv;
+        const float qv = fast_exp2(drow[v] * inv_t_log2 - md) * inv_zd;
+        return fmaxf(pv - qv, 0.f);
+    }
+};
+
+__device__ __forceinline__ AcceptWeight accept_weight(const AcceptParams& p, int b, int n, float mt, float zt, float md, float zd)
+{
+    AcceptWeight w;
+    const bool residual = n < p.gamma;
+    w.trow = p.target + ((int64_t)b * (p.gamma + 1) + n) * p.vocab;
+    w.drow = residual ? p.draft + ((int64_t)b * p.gamma + n) * p.vocab : nullptr;
+    w.inv_t_log2 = p.inv_t_log2;
+    w.mt = mt; w.inv_zt = 1.f / zt;
+    w.md = residual ? md : 0.f; w.inv_zd = residual ? 1.f / zd : 0.f;
+    return w;
+}
+
+__global__ __launch_bounds__(256)
+void accept_mass_partial(const AcceptParams p)
+{
+    __shared__ float s_m[129], s_z[129];        // merged (max, sum) of up to 2*gamma+1 rows
+    __shared__ float s_part[4];
+    __shared__ int s_n;
+    const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rows = 2 * p.gamma + 1;
+    accept_merge_rows(p, b, rows, s_m, s_z);
     __syncthreads();
-    const float* tgt = p.target + (int64_t)b * (p.gamma + 1) * p.vocab;
-    const float* drf = p.draft + (int64_t)b * p.gamma * p.vocab;
-    const int32_t* x = p.tokens + (int64_t)b * p.gamma;
-    const float* u = p.uniforms + (int64_t)b * (p.gamma + 1);
     // The gamma accept tests, one per lane of the first wave (gamma <= 64): every test's loads
     // are in flight together; the first failing test is found by a ballot.
     if (wave == 0) {
+        const float* tgt = p.target + (int64_t)b * (p.gamma + 1) * p.vocab;
+        const float* drf = p.draft + (int64_t)b * p.gamma * p.vocab;
         bool ok = true;
         if (lane < p.gamma) {
-            const int tok = x[lane];
+            const int tok = p.tokens[(int64_t)b * p.gamma + lane];
             ok = tok >= 0 && tok < p.vocab;                      // not a token: cannot be accepted
             if (ok) {
                 const float pt = fast_exp2(tgt[(int64_t)lane * p.vocab + tok] * p.inv_t_log2 - s_m[lane]) / s_z[lane];
                 const float qd = fast_exp2(drf[(int64_t)lane * p.vocab + tok] * p.inv_t_log2 - s_m[p.gamma + 1 + lane]) /
                                  s_z[p.gamma + 1 + lane];
-                ok = u[lane] * qd < pt;
+                ok = p.uniforms[(int64_t)b * (p.gamma + 1) + lane] * qd < pt;
             }
         }
         const uint64_t failed = __ballot(!ok);
-        if (lane == 0) { s_n = failed ? __ffsll((long long)failed) - 1 : p.gamma; s_y = -1; }
+        if (lane == 0) s_n = failed ? __ffsll((long long)failed) - 1 : p.gamma;
     }
     __syncthreads();
     const int n = s_n;
-    const bool residual = n < p.gamma;
-    const float* trow = tgt + (int64_t)n * p.vocab;
-    const float* drow = residual ? drf + (int64_t)n * p.vocab : nullptr;
-    const float mt = s_m[n], inv_zt = 1.f / s_z[n];
-    const float md = residual ? s_m[p.gamma + 1 + n] : 0.f;
-    const float inv_zd = residual ? 1.f / s_z[p.gamma + 1 + n] : 0.f;
-    auto weight = [&](int v) {
-        const float pv = fast_exp2(trow[v] * p.inv_t_log2 - mt) * inv_zt;
-        if (!residual) return pv;
-        const float qv = fast_exp2(drow[v] * p.inv_t_log2 - md) * inv_zd;
-        return fmaxf(pv - qv, 0.f);
-    };
-    // Wave w owns the contiguous token segment [w*seg, (w+1)*seg) and reads it 64 consecutive
-    // tokens at a time (coalesced); wave order = token order.
-    const int seg = ((p.vocab + kAccWaves - 1) / kAccWaves + 63) & ~63;
-    const int lo = min(p.vocab, wave * seg), hi = min(p.vocab, lo + seg);
+    if (chunk == 0) {                                            // what pass 3 needs of the above
+        if (tid < rows) { p.norm[((int64_t)b * rows + tid) * 2] = s_m[tid]; p.norm[((int64_t)b * rows + tid) * 2 + 1] = s_z[tid]; }
+        if (tid == 0) p.n_rej[b] = n;
+    }
+    const int dn = n < p.gamma ? p.gamma + 1 + n : 0;
+    const AcceptWeight weight = accept_weight(p, b, n, s_m[n], s_z[n], s_m[dn], s_z[dn]);
+    const int lo = chunk * kAccChunk, hi = min(p.vocab, lo + kAccChunk);
+    float w[kAccPerThread];
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) {
+        const int v = lo + j * 256 + tid;
+        w[j] = v < hi ? weight(v) : 0.f;
+    }
     float mine = 0.f;
-#pragma unroll 8
-    for (int v = lo + lane; v < hi; v += 64) mine += weight(v);
+#pragma unroll
+    for (int j = 0; j < kAccPerThread; ++j) mine += w[j];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
-    if (lane == 0) s_w[wave] = mine;
+    if (lane == 0) s_part[wave] = mine;
     __syncthreads();
-    float before = 0.f, W = 0.f;
-#pragma unroll
-    for (int w = 0; w < kAccWaves; ++w) {
-        const float y = s_w[w];
-        if (w < wave) before += y;
-        W += y;
-    }
+    if (tid == 0) p.chunk_mass[(int64_t)b * p.n_chunks + chunk] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+}
+
+__global__ __launch_bounds__(kAccThreads)
+void accept_sample_final(const AcceptParams p)
+{
+    __shared__ float s_w[kAccWaves];
+    __shared__ int s_idx[kAccWaves];
+    __shared__ int s_y;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rows = 2 * p.gamma + 1;
+    const int n = p.n_rej[b];
+    const int dn = n < p.gamma ? p.gamma + 1 + n : 0;
+    const float* nm = p.norm + (int64_t)b * rows * 2;
+    const AcceptWeight weight = accept_weight(p, b, n, nm[2 * n], nm[2 * n + 1], nm[2 * dn], nm[2 * dn + 1]);
+    const float* cm = p.chunk_mass + (int64_t)b * p.n_chunks;
+    if (tid == 0) s_y = -1;
+    // total mass and the owner of the goal among the chunks: the LAST chunk with mass whose prefix
+    // does not exceed the goal -- exactly one chunk, whatever rounding did to the sums (a goal that
+    // rounding put at or beyond the total lands on the last chunk with mass).  Every thread walks
+    // the same few numbers in the same order.
+    float W = 0.f;
+    for (int c = 0; c < p.n_chunks; ++c) W += cm[c];
     if (!(W > 0.f)) {
         // no residual mass (p == q): fall back to the target's most likely token
+        const int seg = ((p.vocab + kAccWaves - 1) / kAccWaves + 63) & ~63;
+        const int lo = min(p.vocab, wave * seg), hi = min(p.vocab, lo + seg);
         float bv = 0.f; int bi = -1;
         for (int v = lo + lane; v < hi; v += 64) {
-            const float y = trow[v];
+            const float y = weight.trow[v];
             if (bi < 0 || y > bv) { bv = y; bi = v; }
         }
 #pragma unroll
@@ -223,7 +286,6 @@ void accept_sample_final(const AcceptParams p)
             const int oi = __shfl_xor(bi, off);
             argmax_merge(bv, bi, ov, oi);
         }
-        __syncthreads();                                         // every wave has read s_w
         if (lane == 0) { s_w[wave] = bv; s_idx[wave] = bi; }
         __syncthreads();
         if (tid == 0) {
@@ -232,42 +294,41 @@ void accept_sample_final(const AcceptParams p)
         }
         __syncthreads();
     } else {
-        // The owner of the goal is the LAST wave with mass whose prefix does not exceed it: exactly
-        // one wave, whatever rounding did to the sums (a goal that rounding put at or beyond the
-        // total lands on the last wave with mass).  The search then descends once more: the owner's
-        // segment is dealt to all waves again, and the owner of that level walks its few hundred
-        // tokens 64 at a time for the first token whose cumulative mass passes the goal, else takes
-        // its last token with mass.
-        const float goal = u[p.gamma] * W;
-        auto owner_of = [&](const float* mass, float start, float& prefix) {
-            int owner = -1;
-            float acc = start;
-            prefix = start;
-#pragma unroll
-            for (int w = 0; w < kAccWaves; ++w) {
-                if (mass[w] > 0.f && acc <= goal) { owner = w; prefix = acc; }
-                acc += mass[w];
-            }
-            return owner;
-        };
-        float pre1;
-        const int own1 = owner_of(s_w, 0.f, pre1);
-        const int lo1 = min(p.vocab, own1 * seg), hi1 = min(p.vocab, lo1 + seg);
+        const float goal = p.uniforms[(int64_t)b * (p.gamma + 1) + p.gamma] * W;
+        int own1 = -1;
+        float pre1 = 0.f, acc1 = 0.f;
+        for (int c = 0; c < p.n_chunks; ++c) {
+            const float m = cm[c];
+            if (m > 0.f && acc1 <= goal) { own1 = c; pre1 = acc1; }
+            acc1 += m;
+        }
+        // Inside the owning chunk the same rule picks a wave's share (the chunk is dealt to the
+        // waves in token order), and the owning wave walks its few hundred tokens 64 at a time for
+        // the first token whose cumulative mass passes the goal, else takes its last token with mass.
+        const int lo1 = own1 * kAccChunk, hi1 = min(p.vocab, lo1 + kAccChunk);
         const int seg2 = ((hi1 - lo1 + kAccWaves - 1) / kAccWaves + 63) & ~63;
         const int lo2 = min(hi1, lo1 + wave * seg2), hi2 = min(hi1, lo2 + seg2);
         float mine2 = 0.f;
-#pragma unroll 4
+#pragma unroll 8
         for (int v = lo2 + lane; v < hi2; v += 64) mine2 += weight(v);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) mine2 += __shfl_xor(mine2, off);
-        if (lane == 0) s_w2[wave] = mine2;
+        if (lane == 0) s_w[wave] = mine2;
         __syncthreads();
-        float pre2;
-        const int own2 = owner_of(s_w2, pre1, pre2);
+        int own2 = -1;
+        float pre2 = pre1, acc2 = pre1;
+#pragma unroll
+        for (int w = 0; w < kAccWaves; ++w) {
+            if (s_w[w] > 0.f && acc2 <= goal) { own2 = w; pre2 = acc2; }
+            acc2 += s_w[w];
+        }
+        // (rounding can leave the chunk's own waves without mass although the chunk had some: the
+        // first wave then reports the chunk's last token with mass, or its first token)
+        if (own2 < 0) own2 = 0;
         if (wave == own2) {
             float c = pre2;
             int y = -1, last = -1;
-            for (int base = lo2; base < hi2; base += 64) {       // (at most ten steps at vocab 152 064)
+            for (int base = lo2; base < hi2; base += 64) {       // (at most eight steps)
                 const int v = base + lane;
                 const float w = v < hi2 ? weight(v) : 0.f;
                 float incl = w;
@@ -282,11 +343,12 @@ void accept_sample_final(const AcceptParams p)
                 if (passed && y < 0) y = base + __ffsll((long long)passed) - 1;
                 c += __shfl(incl, 63);
             }
-            if (lane == 0) s_y = y >= 0 ? y : last;
+            if (lane == 0) s_y = y >= 0 ? y : (last >= 0 ? last : lo1);
         }
         __syncthreads();
     }
     if (tid == 0) {
+        const int32_t* x = p.tokens + (int64_t)b * p.gamma;
         int32_t* out = p.out_tokens + (int64_t)b * (p.gamma + 1);
         for (int i = 0; i <= p.gamma; ++i) out[i] = i < n ? x[i] : (i == n ? s_y : -1);
         p.n_accepted[b] = n;
@@ -342,7 +404,12 @@ extern "C" size_t specvlm_accept_workspace_bytes(int batch, int gamma, int vocab
 {
     if (batch <= 0 || gamma < 0 || vocab < 1) return 0;
     const size_t rows = sampling ? 2 * (size_t)gamma + 1 : (size_t)gamma + 1;
-    return 2 * align256((size_t)batch * rows * accept_chunks(vocab) * sizeof(float));
+    size_t bytes = 2 * align256((size_t)batch * rows * accept_chunks(vocab) * sizeof(float));
+    if (sampling)       // merged row statistics, chunk masses of the rejected row, rejected positions
+        bytes += align256((size_t)batch * rows * 2 * sizeof(float)) +
+                 align256((size_t)batch * accept_chunks(vocab) * sizeof(float)) +
+                 align256((size_t)batch * sizeof(int32_t));
+    return bytes;
 }
 
 extern "C" int specvlm_accept(
@@ -369,14 +436,21 @@ extern "C" int specvlm_accept(
     p.batch = batch; p.gamma = gamma; p.vocab = vocab; p.n_chunks = accept_chunks(vocab);
     p.inv_t_log2 = sampling ? kLog2e / temperature : kLog2e;
     p.n_accepted = n_accepted; p.out_tokens = out_tokens;
-    p.part_val = (float*)workspace;
-    p.part_aux = (float*)((char*)workspace + need / 2);
+    const size_t rows = sampling ? 2 * (size_t)gamma + 1 : (size_t)gamma + 1;
+    const size_t part_bytes = align256((size_t)batch * rows * p.n_chunks * sizeof(float));
+    char* ws = (char*)workspace;
+    p.part_val = (float*)ws;
+    p.part_aux = (float*)(ws + part_bytes);
+    p.norm = (float*)(ws + 2 * part_bytes);
+    p.chunk_mass = (float*)((char*)p.norm + align256((size_t)batch * rows * 2 * sizeof(float)));
+    p.n_rej = (int32_t*)((char*)p.chunk_mass + align256((size_t)batch * p.n_chunks * sizeof(float)));
     hipStream_t s = (hipStream_t)stream;
     if (!sampling) {
         hipLaunchKernelGGL(accept_argmax_partial, dim3(p.n_chunks, gamma + 1, batch), dim3(256), 0, s, p);
         hipLaunchKernelGGL(accept_greedy_final, dim3(batch), dim3(64), 0, s, p);
     } else {
         hipLaunchKernelGGL(accept_softmax_partial, dim3(p.n_chunks, 2 * gamma + 1, batch), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(accept_mass_partial, dim3(p.n_chunks, batch), dim3(256), 0, s, p);
         hipLaunchKernelGGL(accept_sample_final, dim3(batch), dim3(kAccThreads), 0, s, p);
     }
     return launch_status();
@@ -408,6 +482,7 @@ extern "C" int specvlm_accept_tree(
     p.n_accepted = n_accepted; p.out_tokens = out_tokens;
     p.part_val = (float*)workspace;
     p.part_aux = (float*)((char*)workspace + need / 2);
+    p.norm = nullptr; p.chunk_mass = nullptr; p.n_rej = nullptr;
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(accept_argmax_partial, dim3(p.n_chunks, n_nodes, batch), dim3(256), 0, s, p);
     hipLaunchKernelGGL(accept_tree_final, dim3(batch), dim3(64), 0, s, p, parent, accepted_nodes);
