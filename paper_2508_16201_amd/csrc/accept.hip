@@ -84,24 +84,35 @@ void accept_argmax_partial(const AcceptParams p)
 __global__ __launch_bounds__(64)
 void accept_greedy_final(const AcceptParams p)
 {
-    // one wave per request; lane i merges the partials of row i (gamma <= 64)
+    // one wave per request; lane i merges the partials of row i and holds drafted token i
+    // (gamma <= 64), the first mismatch is found by a ballot and every lane writes its own output
     const int b = blockIdx.x, lane = threadIdx.x;
     __shared__ int s_t[65];
+    const int32_t* x = p.tokens + (int64_t)b * p.gamma;
+    const int drafted = lane < p.gamma ? x[lane] : -1;           // (in flight while the partials are merged)
     for (int row = lane; row <= p.gamma; row += 64) {
         float bv = 0.f; int bi = -1;
         const int64_t slot = ((int64_t)b * (p.gamma + 1) + row) * p.n_chunks;
-        for (int c = 0; c < p.n_chunks; ++c)
-            argmax_merge(bv, bi, p.part_val[slot + c], __float_as_int(p.part_aux[slot + c]));
+        for (int c0 = 0; c0 < p.n_chunks; c0 += 8) {             // eight chunks' loads in flight at a time
+            float pv[8]; int pi[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool in = c0 + j < p.n_chunks;
+                pv[j] = in ? p.part_val[slot + c0 + j] : 0.f;
+                pi[j] = in ? __float_as_int(p.part_aux[slot + c0 + j]) : -1;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) argmax_merge(bv, bi, pv[j], pi[j]);
+        }
         s_t[row] = bi;
     }
     __syncthreads();
-    if (lane != 0) return;
+    const uint64_t mismatch = __ballot(lane < p.gamma && drafted != s_t[lane]);
+    const int n = mismatch ? __ffsll((long long)mismatch) - 1 : p.gamma;
     int32_t* out = p.out_tokens + (int64_t)b * (p.gamma + 1);
-    const int32_t* x = p.tokens + (int64_t)b * p.gamma;
-    int n = 0;
-    while (n < p.gamma && x[n] == s_t[n]) ++n;
-    for (int i = 0; i <= p.gamma; ++i) out[i] = i < n ? x[i] : (i == n ? s_t[n] : -1);
-    p.n_accepted[b] = n;
+    for (int i = lane; i <= p.gamma; i += 64)
+        out[i] = i < n ? drafted : (i == n ? s_t[n] : -1);       // (i < n implies i = lane < gamma)
+    if (lane == 0) p.n_accepted[b] = n;
 }
 
 // -------------------------------------------------------------- sampling ----
@@ -358,40 +369,52 @@ void accept_sample_final(const AcceptParams p)
 // ------------------------------------------------------------------ tree ----
 // Greedy walk over a static draft tree (App. B): rows of target_logits are tree
 // nodes; node 0 is the last committed token, parent[i] < i.  One wave per
-// request merges the per-chunk argmax partials of every node, then lane 0
-// walks from the root, moving to the lowest-numbered child that drafted the
-// target's token.
+// request: lane i merges the per-chunk argmax partials of node i and holds its
+// parent and drafted token; the wave walks from the root, moving to the
+// lowest-numbered child that drafted the target's token (found by a ballot).
 __global__ __launch_bounds__(64)
 void accept_tree_final(const AcceptParams p, const int32_t* parent, int32_t* accepted_nodes)
 {
     const int b = blockIdx.x, lane = threadIdx.x;
-    const int n_nodes = p.gamma + 1;
-    __shared__ int s_t[65];
-    for (int row = lane; row < n_nodes; row += 64) {
+    const int n_nodes = p.gamma + 1;                             // <= 64: lane i holds node i
+    __shared__ int s_t[64];
+    const int32_t* x = p.tokens + (int64_t)b * n_nodes;
+    const int my_tok = lane < n_nodes ? x[lane] : -1;            // (in flight while the partials are merged)
+    const int my_par = lane < n_nodes ? parent[lane] : -1;       // parent[] is shared by the batch
+    if (lane < n_nodes) {
         float bv = 0.f; int bi = -1;
-        const int64_t slot = ((int64_t)b * n_nodes + row) * p.n_chunks;
-        for (int c = 0; c < p.n_chunks; ++c)
-            argmax_merge(bv, bi, p.part_val[slot + c], __float_as_int(p.part_aux[slot + c]));
-        s_t[row] = bi;
+        const int64_t slot = ((int64_t)b * n_nodes + lane) * p.n_chunks;
+        for (int c0 = 0; c0 < p.n_chunks; c0 += 8) {             // eight chunks' loads in flight at a time
+            float pv[8]; int pi[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool in = c0 + j < p.n_chunks;
+                pv[j] = in ? p.part_val[slot + c0 + j] : 0.f;
+                pi[j] = in ? __float_as_int(p.part_aux[slot + c0 + j]) : -1;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) argmax_merge(bv, bi, pv[j], pi[j]);
+        }
+        s_t[lane] = bi;
     }
     __syncthreads();
-    if (lane != 0) return;
-    const int32_t* x = p.tokens + (int64_t)b * n_nodes;
     int32_t* out = p.out_tokens + (int64_t)b * n_nodes;
     int32_t* nodes = accepted_nodes + (int64_t)b * n_nodes;
+    // the walk: every lane follows it; the children of the current node that drafted the target's
+    // token answer a ballot, the lowest-numbered one is taken (at most n_nodes - 1 steps)
     int cur = 0, n = 0;
+    int my_out = -1, my_node = -1;                               // lane i ends up holding out[i] and nodes[i]
     for (;;) {
         const int t = s_t[cur];
-        int next = -1;
-        for (int c = cur + 1; c < n_nodes && next < 0; ++c)
-            if (parent[c] == cur && x[c] == t) next = c;
-        if (next < 0) { out[n] = t; break; }
-        nodes[n] = next; out[n] = x[next];
+        const uint64_t match = __ballot(lane > cur && lane < n_nodes && my_par == cur && my_tok == t);
+        if (!match) { if (lane == n) my_out = t; break; }
+        const int next = __ffsll((long long)match) - 1;
+        const int tok_next = __shfl(my_tok, next);
+        if (lane == n) { my_node = next; my_out = tok_next; }
         ++n; cur = next;
     }
-    for (int i = n; i < n_nodes; ++i) nodes[i] = -1;
-    for (int i = n + 1; i < n_nodes; ++i) out[i] = -1;
-    p.n_accepted[b] = n;
+    if (lane < n_nodes) { out[lane] = my_out; nodes[lane] = my_node; }
+    if (lane == 0) p.n_accepted[b] = n;
 }
 
 static int accept_chunks(int vocab) { return (vocab + kAccChunk - 1) / kAccChunk; }
