@@ -213,6 +213,8 @@ def test_select_device_side_budget_errors(B):
 @pytest.mark.parametrize("layers,P,V,L,hkv,d,keep_n", [
     (1, 0, 1568, 64, 1, 64, 157), (3, 4, 500, 33, 2, 128, 77), (2, 0, 300, 0, 8, 128, 300),
     (2, 0, 300, 10, 4, 64, 0), (24, 0, 1254, 262, 2, 64, 125),
+    # head counts whose rows are not a power-of-two number of 16-byte chunks (the generic copy kernel)
+    (2, 3, 333, 7, 3, 64, 50), (1, 0, 1000, 5, 5, 128, 100),
 ])
 def test_gather_bit_exact(B, layers, P, V, L, hkv, d, keep_n):
     n_keys = P + V + L
