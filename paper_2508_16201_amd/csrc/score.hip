@@ -27,9 +27,12 @@
 // of pass B therefore holds 64 consecutive queries of ONE q head and its
 // addresses need no per-lane division.
 //
-// The exponentials dominate the arithmetic (one v_exp_f32 per logit, quarter
-// rate); pass A keeps them to one per logit by rescaling its running sum only
-// when a tile's maximum exceeds the reference by more than 2^8.
+// Per logit the VALU issues one fma, one v_exp_f32 (half rate) and one add, as
+// much issue time as the logit's share of the MFMAs: the two streams are
+// interleaved instruction by instruction inside a wave.  Pass A keeps to one
+// exponential per logit: away from the causal mask it does not track maxima at
+// all, and where it does it rescales its running sum only when a tile's maximum
+// exceeds the reference by more than 2^8.
 #include "common.h"
 
 namespace specvlm {
