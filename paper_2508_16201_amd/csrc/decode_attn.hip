@@ -84,19 +84,21 @@ __device__ __forceinline__ int attn_request_tiles(const AttnParams& p, int b, in
     return (ql <= 0 || kvl < ql) ? 0 : (kvl + tile_keys - 1) / tile_keys;
 }
 
-struct AttnBalance { int64_t n_units; int n_wg; };
+struct AttnBalance { int64_t n_units; int n_groups; };
 
-// Total units (tiles x kv heads over the batch) and the number of workgroups that share them:
-// never more workgroups than units, so every workgroup's run is non-empty and the workgroups that
-// touch a (request, head) are consecutive.
+// Balanced mode deals TILES OF REQUESTS (all kv heads of a token range together) to groups of
+// n_kv_heads workgroups, one workgroup per head: n_units = tiles over the batch, n_groups = groups
+// that share them -- never more groups than units, so every group's run is non-empty and the groups
+// that touch a request are consecutive.  The workgroups of a group walk the same token rows at the
+// same time (one DRAM page serves all heads of a token-major cache), and with workgroup ids dealt to
+// the XCDs round-robin a kv head stays on one XCD.
 __device__ __forceinline__ AttnBalance attn_balance(const AttnParams& p, int tile_keys)
 {
     int64_t n = 0;
     for (int b = 0; b < p.batch; ++b) n += attn_request_tiles(p, b, tile_keys);
-    n *= p.n_kv_heads;
     AttnBalance r;
     r.n_units = n;
-    r.n_wg = (int)min((int64_t)p.max_wg, n);
+    r.n_groups = (int)min((int64_t)(p.max_wg / p.n_kv_heads), n);
     return r;
 }
 constexpr int kMaxSplits = 256;
@@ -476,49 +478,50 @@ void attn_split_kernel(const AttnParams p)
         return;
     }
 
-    // Balanced pieces for a batch.  The unit of work is one tile of one (request, kv head); the units
-    // are numbered request-major, then head, then tile, and workgroup w takes the contiguous run
-    // [w*T/W, (w+1)*T/W).  A run that crosses from one (request, head) into the next is cut into
-    // pieces there; piece (w, segment) owns partial slot w + segment, which is unique because from
-    // one piece to the next exactly one of the two grows.  Every workgroup derives the same numbers
-    // from the request lengths, as the merge kernel does.
+    // Balanced pieces for a batch.  The unit of work is one tile of one request (all kv heads); the
+    // units are numbered request-major, then tile, and group j -- workgroups j*H .. j*H+H-1, one per
+    // kv head -- takes the contiguous run [j*T/G, (j+1)*T/G).  A run that crosses from one request
+    // into the next is cut into pieces there; piece (group j, request b) of head g owns partial slot
+    // (j + b)*H + g, unique because from one piece to the next exactly one of j and b grows.  Every
+    // workgroup derives the same numbers from the request lengths, as the merge kernel does.
     const AttnBalance bal = attn_balance(p, TK);
+    const int H = p.n_kv_heads;
     const int w = blockIdx.x;
     if (w == 0) {
         // the merge kernel's view of the decomposition: for every (request, head) its first partial
-        // slot and the number of pieces (the workgroups that touch it are consecutive; the
-        // workgroup that owns unit x is the largest w with w*T/W <= x)
-        for (int seg = threadIdx.x; seg < p.batch * p.n_kv_heads; seg += MB * KS * kWave) {
-            const int sb = seg / p.n_kv_heads, sg = seg % p.n_kv_heads;
+        // slot and the number of pieces (the groups that touch a request are consecutive; the group
+        // that owns unit x is the largest j with j*T/G <= x)
+        for (int seg = threadIdx.x; seg < p.batch * H; seg += MB * KS * kWave) {
+            const int sb = seg / H, sg = seg % H;
             int64_t first = 0;
             for (int bb = 0; bb < sb; ++bb) first += attn_request_tiles(p, bb, TK);
             const int tiles = attn_request_tiles(p, sb, TK);
-            first = first * p.n_kv_heads + (int64_t)sg * tiles;
-            int w_first = 0, live = 0;
+            int j_first = 0, live = 0;
             if (tiles > 0) {
-                w_first = (int)(((first + 1) * bal.n_wg - 1) / bal.n_units);
-                live = (int)(((first + tiles) * bal.n_wg - 1) / bal.n_units) - w_first + 1;
+                j_first = (int)(((first + 1) * bal.n_groups - 1) / bal.n_units);
+                live = (int)(((first + tiles) * bal.n_groups - 1) / bal.n_units) - j_first + 1;
             }
-            p.seg_table[2 * seg] = w_first + seg;
+            p.seg_table[2 * seg] = (j_first + sb) * H + sg;
             p.seg_table[2 * seg + 1] = live;
         }
     }
-    if (w >= bal.n_wg) return;
-    int64_t x = (int64_t)w * bal.n_units / bal.n_wg;
-    const int64_t x_end = (int64_t)(w + 1) * bal.n_units / bal.n_wg;
+    const int j = w / H, g = w % H;
+    if (j >= bal.n_groups) return;
+    int64_t x = (int64_t)j * bal.n_units / bal.n_groups;
+    const int64_t x_end = (int64_t)(j + 1) * bal.n_units / bal.n_groups;
     int b = 0;
     int64_t base = 0;                                   // first unit of request b
     while (x < x_end) {
         int tiles = attn_request_tiles(p, b, TK);
-        while (x >= base + (int64_t)tiles * p.n_kv_heads) {
-            base += (int64_t)tiles * p.n_kv_heads;
+        while (x >= base + tiles) {
+            base += tiles;
             ++b;
             tiles = attn_request_tiles(p, b, TK);
         }
-        const int g = (int)((x - base) / tiles), t = (int)((x - base) % tiles);
+        const int t = (int)(x - base);
         const int n = (int)min((int64_t)(tiles - t), x_end - x);
         const int kvl = p.cu_kv[b + 1] - p.cu_kv[b];
-        piece(b, g, t * TK, min(kvl, (t + n) * TK), (int64_t)(w + b * p.n_kv_heads + g) * p.rows_pad, false);
+        piece(b, g, t * TK, min(kvl, (t + n) * TK), (int64_t)((j + b) * H + g) * p.rows_pad, false);
         x += n;
         __syncthreads();                                // the next piece reuses the ring and the exchange buffer
     }
@@ -640,7 +643,7 @@ void attn_merge_rows_kernel(const AttnParams p)
         for (int i = 0; i < PRE; ++i) {
             m_i[i] = -INFINITY; l_i[i] = 0.f; ov[i] = floatx4{0.f, 0.f, 0.f, 0.f};
             if (s0 + i < live) {
-                const int64_t slot = slot0 + (int64_t)(s0 + i) * p.rows_pad;
+                const int64_t slot = slot0 + (int64_t)(s0 + i) * p.n_kv_heads * p.rows_pad;   // the next group's piece
                 m_i[i] = p.part_ml[slot * 2]; l_i[i] = p.part_ml[slot * 2 + 1];
                 ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
             }
@@ -670,9 +673,9 @@ void attn_merge_rows_kernel(const AttnParams p)
 // ---------------------------------------------------------------- host side ----
 // A batch whose split count is left to the library is cut into balanced pieces by the kernels
 // themselves (they know the request lengths; the host only knows their maximum).
-static bool attn_is_balanced(int batch, int num_splits)
+static bool attn_is_balanced(int batch, int num_splits, int n_kv_heads)
 {
-    return batch > 1 && batch <= kMaxBalancedBatch && num_splits == 0;
+    return batch > 1 && batch <= kMaxBalancedBatch && num_splits == 0 && n_kv_heads <= kNumCu;
 }
 
 static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
@@ -771,7 +774,7 @@ extern "C" size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int 
     if (rows > 64) return 0;
     const int rows_pad = round_up(rows, 16);
     size_t slots;
-    if (attn_is_balanced(batch, num_splits)) {
+    if (attn_is_balanced(batch, num_splits, n_kv_heads)) {
         slots = (size_t)(kNumCu + batch * n_kv_heads) * rows_pad;
         return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) +
                align256((size_t)batch * n_kv_heads * 2 * sizeof(int32_t));
@@ -820,7 +823,7 @@ static int attn_impl(
     p.batch = batch; p.q_len = q_len; p.kv_len = kv_len;
     p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = group;
     p.scale_log2 = softmax_scale * kLog2e;
-    p.balanced = attn_is_balanced(batch, num_splits) ? 1 : 0;
+    p.balanced = attn_is_balanced(batch, num_splits, n_kv_heads) ? 1 : 0;
     p.max_wg = kNumCu;
     p.tile_keys = mb == 1 ? 128 : 64;                 // TK of the launch shape chosen below
     p.num_splits = p.balanced ? 2 : choose_splits(batch, kv_len, n_kv_heads, num_splits);
