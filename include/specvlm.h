@@ -197,9 +197,10 @@ int specvlm_gather_kv(
  *   num_splits: key-range splits per (request, kv head) (flash-decode);
  *               0 lets the library choose for the shape.  For a batch of 2..64
  *               requests the choice is made on the device from the request
- *               lengths: the key tiles of all (request, kv head) pairs are dealt
- *               in equal contiguous runs to one workgroup per CU, so requests of
- *               very different lengths finish together.
+ *               lengths: the key tiles of the requests are dealt in equal
+ *               contiguous runs to groups of n_kv_heads workgroups (one per
+ *               head, one workgroup per CU), so requests of very different
+ *               lengths finish together.
  *   Workspace: the query takes the same batch, maxima, head counts and
  *               num_splits as the call (it is pure: it depends on nothing else).
  * Limits: (H_q/H_kv) * q_len <= 64.
