@@ -86,9 +86,16 @@ int specvlm_version(void);
  *   scores   fp32 [n_video]:  scores = beta * scores + (1/(H_q n_text)) sum_{h,i} G
  *            (beta = 0 overwrites and never reads the old contents)
  *
- * One request per call: cu_text, cu_keys and cu_video must be NULL and batch 1
- * (a batch is scored by one call per request); other values return
- * SPECVLM_EUNSUPPORTED.
+ * A batch: the requests are concatenated along the token axis of q_text,
+ * k_cache, row_lse and scores, and cu_text, cu_keys, cu_video are HOST int32
+ * arrays of batch+1 prefix offsets (unlike the other calls' device arrays: the
+ * split plan of every request is made on the host, and scoring happens at
+ * prefill, when the host knows the lengths).  n_text, n_keys, n_video are then
+ * the maxima over the batch; video_start applies inside every request;
+ * text_pos0 = -1 places each request's text queries on its last n_text_b keys
+ * (text_pos0 >= 0 is the same position for every request).  The requests are
+ * enqueued one after the other and share the workspace; every request is
+ * validated before the first launch.  With all three NULL, batch must be 1.
  * -------------------------------------------------------------------------- */
 size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_keys, int n_video,
                                      int n_q_heads, int n_kv_heads, int head_dim,

@@ -11,6 +11,7 @@ import ctypes as C
 import os
 from typing import Optional, Tuple
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -128,28 +129,50 @@ def _thd(t: torch.Tensor) -> Tuple[int, int]:
 
 # --------------------------------------------------------------------------- score
 def score_workspace_bytes(n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_dim,
-                          have_row_lse=False) -> int:
-    return lib().specvlm_score_workspace_bytes(1, n_text, n_keys, n_video, n_q_heads, n_kv_heads,
+                          have_row_lse=False, batch=1) -> int:
+    return lib().specvlm_score_workspace_bytes(batch, n_text, n_keys, n_video, n_q_heads, n_kv_heads,
                                                head_dim, int(have_row_lse))
+
+
+def _host_i32(a):
+    """Host int32 prefix offsets for specvlm_score (which plans every request on the host)."""
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+    return arr, arr.ctypes.data_as(C.c_void_p)
 
 
 def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
           text_pos0: int, softmax_scale: float, *, norm_mode: int = 0,
           row_lse: Optional[torch.Tensor] = None, beta: float = 0.0,
-          scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
-          ) -> torch.Tensor:
-    """q_text [L,H_q,d] bf16, k_cache [n_keys,H_kv,d] bf16 -> scores fp32 [n_video]."""
+          scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+          cu_text=None, cu_keys=None, cu_video=None) -> torch.Tensor:
+    """q_text [L,H_q,d] bf16, k_cache [n_keys,H_kv,d] bf16 -> scores fp32 [n_video].
+
+    A batch: requests concatenated along the token axis, cu_text / cu_keys / cu_video = HOST int32
+    prefix offsets [batch+1]; n_video is then ignored (taken from cu_video) and text_pos0 = -1 places
+    every request's text queries on its last keys."""
     n_text, hq, d = q_text.shape
     n_keys, hkv, _ = k_cache.shape
+    batch, ptrs, keep_alive = 1, (None, None, None), []
+    if cu_text is not None:
+        hosts = [_host_i32(a) for a in (cu_text, cu_keys, cu_video)]
+        keep_alive = [h[0] for h in hosts]
+        ptrs = tuple(h[1] for h in hosts)
+        batch = len(keep_alive[0]) - 1
+        total_video = int(keep_alive[2][-1])
+        n_text = int(np.diff(keep_alive[0]).max()) if batch else 0
+        n_keys = int(np.diff(keep_alive[1]).max()) if batch else 0
+        n_video = int(np.diff(keep_alive[2]).max()) if batch else 0
+    else:
+        total_video = n_video
     if scores is None:
-        scores = torch.empty(n_video, dtype=torch.float32, device=q_text.device)
+        scores = torch.empty(total_video, dtype=torch.float32, device=q_text.device)
         if beta != 0.0:
             raise ValueError("beta != 0 needs an existing scores tensor")
-    need = score_workspace_bytes(n_text, n_keys, n_video, hq, hkv, d, row_lse is not None)
+    need = score_workspace_bytes(n_text, n_keys, n_video, hq, hkv, d, row_lse is not None, batch=max(batch, 1))
     workspace = _ws(workspace, need, q_text)
     qs, ks = _thd(q_text), _thd(k_cache)
     rc = lib().specvlm_score(_ptr(q_text), qs[0], qs[1], _ptr(k_cache), ks[0], ks[1],
-                             None, None, None, 1, n_text, n_keys, video_start, n_video, text_pos0,
+                             ptrs[0], ptrs[1], ptrs[2], batch, n_text, n_keys, video_start, n_video, text_pos0,
                              hq, hkv, d, float(softmax_scale), norm_mode, _ptr(row_lse),
                              float(beta), _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
     _check("specvlm_score", rc)

@@ -44,6 +44,8 @@ constexpr int kScoreTile = 64;         // streamed vectors per LDS tile
 constexpr int kScoreBlock = 256;       // stationary vectors per workgroup
 constexpr int kScoreStages = 3;        // LDS ring depth
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
+constexpr int kMaxSplitsA = 64;        // key-range splits of pass A, at most
+constexpr int kMaxSplitsB = 16;        // row-range splits of pass B, at most
 constexpr float kLazyMargin = 8.f;     // log2 units of headroom before the running sum is rescaled
 constexpr float kSumRedo = 0x1p100f;   // a running sum at or above this (or NaN) is recomputed with maxima tracked
 
@@ -518,9 +520,9 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
     };
     const int dom = s.key_hi - s.key_lo;
     const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
-    s.a_splits = best_splits(blocks_a, dom, 64, &s.a_split_keys);
+    s.a_splits = best_splits(blocks_a, dom, kMaxSplitsA, &s.a_split_keys);
     const int blocks_b = (s.video_pad / kScoreBlock) * n_kv_heads;
-    s.b_splits = best_splits(blocks_b, s.rows, 16, &s.b_split_rows);
+    s.b_splits = best_splits(blocks_b, s.rows, kMaxSplitsB, &s.b_split_rows);
     size_t off = 0;
     s.off_ml = off;
     if (!have_row_lse) off += align256((size_t)n_kv_heads * s.rows_pad * s.a_splits * 2 * sizeof(float));
@@ -538,45 +540,47 @@ extern "C" size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_key
                                                 int n_q_heads, int n_kv_heads, int head_dim,
                                                 int have_row_lse)
 {
-    if (batch != 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
+    if (batch < 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
         n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
         return 0;
+    if (batch > 1) {
+        // The requests of a batch are scored one after the other in the same workspace, each with
+        // the split plan of its own sizes; the arguments are the maxima over the batch.  Bound every
+        // plan: at most kMaxSplitsA key splits and kMaxSplitsB row splits, rows and columns padded.
+        const int group = n_q_heads / n_kv_heads;
+        const size_t rows_pad = (size_t)round_up(group * round_up(n_text > 0 ? n_text : 1, kScoreTile), kScoreBlock);
+        const size_t video_pad = (size_t)round_up(n_video > 0 ? n_video : 1, kScoreBlock);
+        size_t total = align256((size_t)n_kv_heads * rows_pad * sizeof(float)) +
+                       align256((size_t)n_kv_heads * kMaxSplitsB * video_pad * sizeof(float));
+        if (!have_row_lse) total += align256((size_t)n_kv_heads * rows_pad * kMaxSplitsA * 2 * sizeof(float));
+        return total;
+    }
     // the split plan depends on the normalisation domain; size for the larger one
     const ScorePlan a = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
     const ScorePlan b = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
     return a.total > b.total ? a.total : b.total;
 }
 
-extern "C" int specvlm_score(
+// One request: validation without side effects (launch == false), or the launches.
+static int score_one(
     const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
     const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
-    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
     int n_text, int n_keys, int video_start, int n_video, int text_pos0,
     int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
     int norm_mode, const float* row_lse, float beta, float* scores,
-    void* workspace, size_t workspace_bytes, void* stream)
+    void* workspace, size_t workspace_bytes, void* stream, bool launch)
 {
-    if (batch < 0 || n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0 || text_pos0 < 0)
-        return SPECVLM_EINVAL;
-    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads) return SPECVLM_EINVAL;
+    if (n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0 || text_pos0 < 0) return SPECVLM_EINVAL;
     if ((int64_t)video_start + n_video > n_keys) return SPECVLM_EINVAL;
-    if (norm_mode != 0 && norm_mode != 1) return SPECVLM_EINVAL;
-    if (!(softmax_scale >= 0.f) || !(softmax_scale < INFINITY)) return SPECVLM_EINVAL;
-    if (head_dim != 64 && head_dim != 128) return SPECVLM_EUNSUPPORTED;
-    if (batch == 0 || n_video == 0) return SPECVLM_OK;
-    if (cu_text || cu_keys || cu_video || batch != 1) return SPECVLM_EUNSUPPORTED;   // one request per call
+    if (n_video == 0) return SPECVLM_OK;
     if (!scores) return SPECVLM_EINVAL;
     if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
-    if ((q_tok_stride | q_head_stride | k_tok_stride | k_head_stride) & 7) return SPECVLM_EUNSUPPORTED;
     if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
-    // a lane's byte offset inside a 64-vector tile is kept in 32 bits
-    if (q_tok_stride < 0 || k_tok_stride < 0 || q_tok_stride >= (1 << 24) || k_tok_stride >= (1 << 24))
-        return SPECVLM_EUNSUPPORTED;
 
     const ScorePlan plan = score_plan(n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
                                       head_dim, norm_mode, row_lse != nullptr);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.total) return SPECVLM_EWORKSPACE;
-
+    if (!launch) return SPECVLM_OK;
     ScoreParams p;
     p.q = (const __bf16*)q_text; p.k = (const __bf16*)k_cache;
     p.q_tok = q_tok_stride; p.q_head = q_head_stride; p.k_tok = k_tok_stride; p.k_head = k_head_stride;
@@ -614,4 +618,51 @@ extern "C" int specvlm_score(
     }
     hipLaunchKernelGGL(score_final_kernel, dim3((n_video + 255) / 256), dim3(256), 0, s, p);
     return launch_status();
+}
+
+extern "C" int specvlm_score(
+    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch < 0 || text_pos0 < -1) return SPECVLM_EINVAL;
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads) return SPECVLM_EINVAL;
+    if (norm_mode != 0 && norm_mode != 1) return SPECVLM_EINVAL;
+    if (!(softmax_scale >= 0.f) || !(softmax_scale < INFINITY)) return SPECVLM_EINVAL;
+    if (head_dim != 64 && head_dim != 128) return SPECVLM_EUNSUPPORTED;
+    if ((q_tok_stride | q_head_stride | k_tok_stride | k_head_stride) & 7) return SPECVLM_EUNSUPPORTED;
+    // a lane's byte offset inside a 64-vector tile is kept in 32 bits
+    if (q_tok_stride < 0 || k_tok_stride < 0 || q_tok_stride >= (1 << 24) || k_tok_stride >= (1 << 24))
+        return SPECVLM_EUNSUPPORTED;
+    if (batch == 0) return SPECVLM_OK;
+    const bool ragged = cu_text || cu_keys || cu_video;
+    if (ragged && !(cu_text && cu_keys && cu_video)) return SPECVLM_EINVAL;
+    if (!ragged && batch != 1) return SPECVLM_EINVAL;
+    // Two passes over the requests: every request is validated (sizes, workspace) before the first
+    // launch, so a failed call has enqueued nothing.  The requests run one after the other on the
+    // stream and share the workspace.
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int b = 0; b < batch; ++b) {
+            int nt = n_text, nk = n_keys, nv = n_video;
+            int64_t t0 = 0, k0 = 0, v0 = 0;
+            if (ragged) {
+                t0 = cu_text[b]; k0 = cu_keys[b]; v0 = cu_video[b];
+                nt = cu_text[b + 1] - cu_text[b]; nk = cu_keys[b + 1] - cu_keys[b]; nv = cu_video[b + 1] - cu_video[b];
+                if (nt > n_text || nk > n_keys || nv > n_video) return SPECVLM_EINVAL;   // the scalars are the maxima
+            }
+            const int pos0 = text_pos0 >= 0 ? text_pos0 : nk - nt;     // -1: the text queries are the last keys
+            const int rc = score_one(
+                (const __bf16*)q_text + t0 * q_tok_stride, q_tok_stride, q_head_stride,
+                (const __bf16*)k_cache + k0 * k_tok_stride, k_tok_stride, k_head_stride,
+                nt, nk, video_start, nv, pos0, n_q_heads, n_kv_heads, head_dim, softmax_scale, norm_mode,
+                row_lse ? row_lse + t0 * n_q_heads : nullptr, beta, scores ? scores + v0 : nullptr,
+                workspace, workspace_bytes, stream, pass == 1);
+            if (rc != SPECVLM_OK) return rc;
+        }
+    }
+    return SPECVLM_OK;
 }

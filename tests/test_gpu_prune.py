@@ -141,6 +141,31 @@ def test_score_planted_keys_on_top_and_chain_to_select(B):
         assert abs(want[j] - kth) <= 1e-3 * kth
 
 
+def test_score_ragged_batch_equals_per_request_oracle(B):
+    """Three requests of different video and prompt lengths in one call (host prefix offsets): every
+    request's scores equal the oracle's for that request alone, for both normalisation domains,
+    with and without accumulation into existing scores."""
+    hq, hkv, d = 8, 2, 128
+    Vs, Ls = [700, 196, 1300], [40, 70, 9]
+    qs = [rnd_bits((L, hq, d), 300 + i) for i, L in enumerate(Ls)]
+    ks = [rnd_bits((V + L, hkv, d), 310 + i) for i, (V, L) in enumerate(zip(Vs, Ls))]
+    cu_text = np.concatenate([[0], np.cumsum(Ls)])
+    cu_keys = np.concatenate([[0], np.cumsum([V + L for V, L in zip(Vs, Ls)])])
+    cu_video = np.concatenate([[0], np.cumsum(Vs)])
+    qd, kd = dev_bf16(np.concatenate(qs)), dev_bf16(np.concatenate(ks))
+    scale = 1.0 / np.sqrt(d)
+    for mode in (0, 1):
+        got = B.score(qd, kd, 0, 0, -1, scale, norm_mode=mode, cu_text=cu_text, cu_keys=cu_keys, cu_video=cu_video)
+        again = B.score(qd, kd, 0, 0, -1, scale, norm_mode=mode, beta=1.0, scores=got.clone(),
+                        cu_text=cu_text, cu_keys=cu_keys, cu_video=cu_video)
+        torch.cuda.synchronize()
+        for i, (V, L) in enumerate(zip(Vs, Ls)):
+            want = oracle.score(qs[i], ks[i], 0, V, V, scale, norm_mode=mode)
+            sl = slice(int(cu_video[i]), int(cu_video[i + 1]))
+            assert_scores_close(got[sl], want, f"request {i} mode{mode}")
+            assert_scores_close(again[sl], 2 * want, f"request {i} mode{mode} accumulated")
+
+
 def test_score_argument_errors(B):
     q = torch.zeros((4, 4, 64), dtype=torch.bfloat16, device="cuda")
     k = torch.zeros((20, 1, 64), dtype=torch.bfloat16, device="cuda")
@@ -149,6 +174,11 @@ def test_score_argument_errors(B):
     assert e.value.status == -1
     with pytest.raises(B.SpecVLMError):
         B.score(q, k, 0, 16, 16, 0.1, norm_mode=3)
+    q8 = torch.zeros((8, 4, 64), dtype=torch.bfloat16, device="cuda")
+    k40 = torch.zeros((40, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.SpecVLMError) as e:          # the second request's video span exceeds its keys
+        B.score(q8, k40, 0, 0, -1, 0.1, cu_text=[0, 4, 8], cu_keys=[0, 30, 40], cu_video=[0, 10, 26])
+    assert e.value.status == -1
 
 
 # ----------------------------------------------------------------- select
