@@ -691,9 +691,9 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
         // 4.9 TB/s with 24, 4.2 TB/s with 32).
         s = (kTargetWorkgroups + heads - 1) / heads;
         if (batch > 1) {
-            // Ragged batches: cap a split at 2048 keys so that long and short requests decompose
-            // into similar pieces the dispatcher can balance; two workgroups are resident per CU
-            // (64 KB of LDS ring each), and a launch of several rounds is made a whole number of them.
+            // Batches too large for the balanced decomposition: cap a split at 2048 keys so that
+            // long and short requests decompose into similar pieces the dispatcher can balance,
+            // and make a launch of several rounds a whole number of rounds of 2 x 256 workgroups.
             const int by_len = (kv_len + 2047) / 2048;
             if (by_len > s) s = by_len;
             const int slots = 2 * kNumCu;
