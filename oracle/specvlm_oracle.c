@@ -218,9 +218,19 @@ int oracle_select(const float* scores, int n_video, int k_top, int keep_budget,
 }
 
 /* Stage I's own size rule (Eq. 6): the smallest c such that the c largest
- * scores sum to at least lambda times the total.  Sums in fp64 in sorted
- * order.  Returns c, or a negative error.  *margin (optional) receives the distance
- * of lambda*total to the nearer of the two prefix sums that decide c, divided by the total. */
+ * scores sum to at least lambda times the total.  The scores of Eq. 6 are
+ * attention masses (means of softmax probabilities, Eq. 5), so a value that is
+ * not a finite positive number (negative, zero, NaN, infinite) carries no
+ * mass; it keeps its place in the descending order.  The total is the last
+ * prefix sum (fp64, in sorted order), so lambda = 1 is reached exactly where
+ * the mass ends.  Returns c, or a negative error.  *margin (optional) receives
+ * the distance of lambda*total to the nearer of the two prefix sums that
+ * decide c, divided by the total. */
+static double score_mass(float x)
+{
+    return (x > 0.0f && x < INFINITY) ? (double)x : 0.0;
+}
+
 int oracle_top_p_count(const float* scores, int n_video, double lambda, double* margin)
 {
     if (n_video < 0 || !(lambda >= 0.0 && lambda <= 1.0)) return -1;
@@ -228,15 +238,13 @@ int oracle_top_p_count(const float* scores, int n_video, double lambda, double* 
     if (n_video == 0) return 0;
     scored_t* order = (scored_t*)malloc(sizeof(scored_t) * (size_t)n_video);
     if (!order) return -2;
-    double total = 0.0;
-    for (int j = 0; j < n_video; ++j) {
-        order[j].key = scores[j]; order[j].idx = j;
-        total += (double)scores[j];
-    }
+    for (int j = 0; j < n_video; ++j) { order[j].key = scores[j]; order[j].idx = j; }
     qsort(order, (size_t)n_video, sizeof(scored_t), cmp_desc);
+    double total = 0.0;
+    for (int j = 0; j < n_video; ++j) total += score_mass(order[j].key);
     double acc = 0.0, before = 0.0;
     int c = 0;
-    while (c < n_video && !(acc >= lambda * total)) { before = acc; acc += (double)order[c].key; ++c; }
+    while (c < n_video && !(acc >= lambda * total)) { before = acc; acc += score_mass(order[c].key); ++c; }
     /* margin: how far the threshold sits from the two partial sums that decide c, relative to the total */
     if (margin && total > 0.0) {
         const double goal = lambda * total;

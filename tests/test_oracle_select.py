@@ -122,3 +122,30 @@ def test_top_p_count_is_minimal_prefix():
         srt = np.sort(s.astype(np.float64))[::-1]
         cs = np.cumsum(srt)
         assert cs[c - 1] >= lam * cs[-1] * (1 - 1e-12) and (c == 1 or cs[c - 2] < lam * cs[-1] * (1 + 1e-12))
+
+
+def test_top_p_count_values_without_mass():
+    """Eq. 6 sums attention masses: a score that is not a finite positive number (negative, zero,
+    NaN, infinite) adds nothing but keeps its place in the descending order.  Worked by hand."""
+    s = np.array([0.5, -1.0, 0.25, np.nan, 0.25, 0.0, -0.0], np.float32)
+    # descending: .5 .25 .25 0 -0 -1 NaN ; masses .5 .25 .25 0 0 0 0 ; total 1
+    assert oracle.top_p_count(s, 0.0) == 0
+    assert oracle.top_p_count(s, 0.5) == 1             # .5 >= .5
+    assert oracle.top_p_count(s, 0.6) == 2             # .75 >= .6
+    assert oracle.top_p_count(s, 0.75) == 2
+    assert oracle.top_p_count(s, 0.76) == 3
+    assert oracle.top_p_count(s, 1.0) == 3             # the mass ends at the third token
+    c, m = oracle.top_p_count(s, 0.6, want_margin=True)
+    assert c == 2 and abs(m - 0.1) < 1e-12             # prefix sums .5 | .75 around the goal .6
+    # the raw sum of this vector is 0 (the -1 cancels the mass): a rule that summed raw values would return 0
+    assert float(np.nansum(s.astype(np.float64))) == 0.0
+    # an infinite score ranks first and carries no mass: it is counted on the way to the first unit score
+    s = np.array([1.0, np.inf, 1.0], np.float32)
+    assert oracle.top_p_count(s, 0.5) == 2 and oracle.top_p_count(s, 1.0) == 3
+    # nothing with mass at all
+    assert oracle.top_p_count(np.array([-1.0, np.nan, 0.0], np.float32), 0.7) == 0
+    # lambda = 1 stops exactly at the last positive score, whatever the order of the input
+    s = synth.make_scores(5000, 21)
+    s[::7] = 0.0
+    s[3::11] = -s[3::11]
+    assert oracle.top_p_count(s, 1.0) == int((s > 0).sum())
