@@ -151,8 +151,9 @@ int specvlm_select(
  * least lambda times the sum of all scores (0 when the total is 0 or lambda
  * is 0), clamped to max_count[b] when max_count is given.  The result can be
  * passed to specvlm_select as k_top (with max_count = keep_budget).
- * Scores are attention masses: values that are not > 0 (negatives, NaN) count
- * as 0.  Sums are exact 64-bit fixed point (2^-40 of the largest score), so the
+ * Scores are attention masses: a value that is not a finite positive number
+ * (negative, zero, NaN, infinite) adds no mass and keeps its place in the
+ * descending order.  Sums are exact 64-bit fixed point (2^-40 of the largest score), so the
  * result is deterministic; it can differ from an fp64 evaluation only when
  * lambda * total lies within ~1e-9 * total of a prefix sum.
  *   scores fp32 [sum n_video_b]; cu_video int32 [batch+1] or NULL (batch 1);
@@ -179,6 +180,22 @@ int specvlm_top_p_count(
  * n_keys - n_video + n_keep tokens per layer.  keep_idx is device int32
  * [n_keep], video-local, ascending (the output of specvlm_select).  dst must
  * not overlap src.  v_src/v_dst may both be NULL to copy K only.
+ *
+ * A batch (one launch for all requests): the requests are concatenated along
+ * the token axis of src, dst and keep_idx; cu_keys, cu_video, cu_keep are
+ * device int32 [batch+1] prefix offsets of the requests' source rows, video
+ * tokens and kept tokens (cu_video and cu_keep are the arrays specvlm_select
+ * takes), and n_keys, n_video, n_keep are the TOTALS over the batch (host
+ * ints: they size the launch).  Request b's destination rows start at
+ * cu_keys[b] - cu_video[b] + cu_keep[b]; video_start applies inside every
+ * request.  All three NULL: one request (batch must be 0 or 1).
+ *
+ *   status  optional device int32 [1]: SPECVLM_OK, or SPECVLM_EINVAL when some
+ *           keep_idx entry lies outside its request's video span or a request's
+ *           device-side sizes do not fit together (n_keep_b > n_video_b,
+ *           video_start + n_video_b > n_keys_b).  A destination row without a
+ *           valid source is zero-filled; nothing is read out of bounds.  With
+ *           status NULL the same rows are zero-filled silently.
  * -------------------------------------------------------------------------- */
 int specvlm_gather_kv(
     const void* k_src, const void* v_src,
@@ -186,7 +203,9 @@ int specvlm_gather_kv(
     void* k_dst, void* v_dst,
     int64_t dst_layer_stride, int64_t dst_tok_stride, int64_t dst_head_stride,
     int n_layers, int n_keys, int video_start, int n_video,
-    const int32_t* keep_idx, int n_keep, int n_kv_heads, int head_dim, void* stream);
+    const int32_t* keep_idx, int n_keep,
+    const int32_t* cu_keys, const int32_t* cu_video, const int32_t* cu_keep, int batch,
+    int32_t* status, int n_kv_heads, int head_dim, void* stream);
 
 /* --------------------------------------------------------------------------
  * specvlm_decode_attn -- grouped-query softmax attention of a short query

@@ -50,7 +50,7 @@ def lib() -> C.CDLL:
         l.specvlm_status_string.argtypes = [C.c_int]
         l.specvlm_version.restype = C.c_int
         for name in EXPORTS:
-            if name.endswith("_workspace_bytes"):
+            if name.endswith("_workspace_bytes") or name.endswith("_scratch_bytes"):
                 getattr(l, name).restype = C.c_size_t
         i64, i32, f32, vp, sz = C.c_int64, C.c_int, C.c_float, C.c_void_p, C.c_size_t
         l.specvlm_score_workspace_bytes.argtypes = [i32] * 8
@@ -62,7 +62,7 @@ def lib() -> C.CDLL:
         l.specvlm_top_p_count_workspace_bytes.argtypes = [i32, i32]
         l.specvlm_top_p_count.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, sz, vp]
         l.specvlm_gather_kv.argtypes = [vp, vp, i64, i64, i64, vp, vp, i64, i64, i64,
-                                        i32, i32, i32, i32, vp, i32, i32, i32, vp]
+                                        i32, i32, i32, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp]
         l.specvlm_decode_attn_workspace_bytes.argtypes = [i32] * 7
         l.specvlm_decode_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
                                           i32, i32, i32, f32, vp, vp, i32, vp, sz, vp]
@@ -78,7 +78,8 @@ def lib() -> C.CDLL:
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
         for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
-                     "specvlm_decode_attn", "specvlm_accept", "specvlm_tree_attn", "specvlm_accept_tree"):
+                     "specvlm_decode_attn", "specvlm_accept", "specvlm_tree_attn",
+                     "specvlm_accept_tree"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -223,13 +224,19 @@ def top_p_count(scores: torch.Tensor, lam: float, *, cu_video: Optional[torch.Te
 # ----------------------------------------------------------------------- gather_kv
 def gather_kv(k_src: torch.Tensor, v_src: Optional[torch.Tensor], video_start: int, n_video: int,
               keep_idx: torch.Tensor, k_dst: Optional[torch.Tensor] = None,
-              v_dst: Optional[torch.Tensor] = None):
-    """k_src/v_src bf16 [layers, n_keys, H_kv, d] (any layer/token/head strides, d contiguous)."""
+              v_dst: Optional[torch.Tensor] = None, *, cu_keys: Optional[torch.Tensor] = None,
+              cu_video: Optional[torch.Tensor] = None, cu_keep: Optional[torch.Tensor] = None,
+              want_status: bool = False):
+    """k_src/v_src bf16 [layers, n_keys, H_kv, d] (any layer/token/head strides, d contiguous).
+
+    A batch: requests concatenated along the token axis, cu_keys / cu_video / cu_keep device int32
+    [batch+1]; n_video is then the total over the batch."""
     if k_src.dim() != 4 or k_src.stride(3) != 1:
         raise ValueError("expected [layers, tokens, heads, d] with contiguous d")
     n_layers, n_keys, hkv, d = k_src.shape
     n_keep = keep_idx.numel()
     n_dst = n_keys - n_video + n_keep
+    batch = 1 if cu_keys is None else cu_keys.numel() - 1
     if k_dst is None:
         k_dst = torch.empty((n_layers, n_dst, hkv, d), dtype=k_src.dtype, device=k_src.device)
     if v_src is not None and v_dst is None:
@@ -238,12 +245,14 @@ def gather_kv(k_src: torch.Tensor, v_src: Optional[torch.Tensor], video_start: i
         raise ValueError("K and V must share strides")
     if v_dst is not None and v_dst.stride() != k_dst.stride():
         raise ValueError("K and V destinations must share strides")
+    status = torch.empty(1, dtype=torch.int32, device=k_src.device) if want_status else None
     rc = lib().specvlm_gather_kv(_ptr(k_src), _ptr(v_src), k_src.stride(0), k_src.stride(1),
                                  k_src.stride(2), _ptr(k_dst), _ptr(v_dst), k_dst.stride(0),
                                  k_dst.stride(1), k_dst.stride(2), n_layers, n_keys, video_start,
-                                 n_video, _ptr(keep_idx), n_keep, hkv, d, _stream())
+                                 n_video, _ptr(keep_idx), n_keep, _ptr(cu_keys), _ptr(cu_video),
+                                 _ptr(cu_keep), batch, _ptr(status), hkv, d, _stream())
     _check("specvlm_gather_kv", rc)
-    return k_dst, v_dst
+    return (k_dst, v_dst, status) if want_status else (k_dst, v_dst)
 
 
 # --------------------------------------------------------------------- decode_attn

@@ -43,6 +43,8 @@
 //     contraction order over keys and the column order of O are permutations
 //     fixed by this layout.  O^T keeps row r in lane column r too, so the
 //     running-max rescale is a per-lane multiply.
+#include <atomic>
+
 #include "common.h"
 
 namespace specvlm {
@@ -102,6 +104,7 @@ __device__ __forceinline__ AttnBalance attn_balance(const AttnParams& p, int til
     return r;
 }
 constexpr int kMaxSplits = 256;
+constexpr int kMaxDevices = 64;         // per-device host state (kernel attributes, scratch addresses)
 constexpr int kTargetWorkgroups = 192;  // workgroups of a single-request launch
 
 // s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n only.
@@ -718,12 +721,15 @@ static int launch_attn_s(const AttnParams& p, hipStream_t stream)
     constexpr size_t merge = KS > 1 ? sizeof(float) * (size_t)(2 * NW * 16 + NW * 16 * (D + 4)) : 0;
     constexpr size_t lds = ring > merge ? ring : merge;
     if (lds > 64 * 1024) {
-        static bool raised = false;
-        if (!raised) {
+        // the attribute belongs to the kernel as loaded on one device: raise it once per device
+        static std::atomic<bool> raised[kMaxDevices];
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECVLM_ELAUNCH;
+        if (!raised[dev].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS, STREAM>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return SPECVLM_ELAUNCH;
-            raised = true;
+            raised[dev].store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, STREAM>), dim3(p.n_work), dim3(NW * kWave),

@@ -86,7 +86,7 @@ void select_kernel(const SelectParams p)
     }
     const int k = p.k_top[b], budget = p.keep_budget[b];
     const int out0 = p.cu_keep ? p.cu_keep[b] : 0;
-    const bool bad = n < 0 || n > E * kSelThreads || k < 0 || k > budget || budget > n;
+    const bool bad = n < 0 || n > E * kSelThreads || n > p.max_n_video || k < 0 || k > budget || budget > n;
     if (p.status && tid == 0) p.status[b] = bad ? SPECVLM_EINVAL : SPECVLM_OK;
     if (bad || budget == 0) return;
 
@@ -236,7 +236,8 @@ void select_kernel(const SelectParams p)
 // the selection, but the per-digit histograms carry SUMS as well as counts.
 // Sums are 64-bit fixed point (score * 2^40 / max score): integer adds commute,
 // so the result does not depend on the order in which lanes reach the atomics.
-// Scores are attention masses (>= 0); negative values and NaN count as 0.
+// Scores are attention masses: a value that is not a finite positive number
+// counts as 0 (and keeps its place in the descending order).
 struct TopPParams {
     const float* scores;
     const int32_t* cu_video;
@@ -268,6 +269,8 @@ void top_p_kernel(const TopPParams p)
     const int first = tid * per;
     const float* sc = p.scores + v0;
 
+    // a value that is not a finite positive number carries no mass; its key still ranks it
+    auto mass_of = [](float x) { return (x > 0.f && x < INFINITY) ? x : 0.f; };
     float val[E];
     uint64_t valid = 0;
     float mx = 0.f;
@@ -275,11 +278,9 @@ void top_p_kernel(const TopPParams p)
     for (int e = 0; e < E; ++e) {
         const int idx = first + e;
         const bool ok = e < per && idx < n;
-        float x = ok ? sc[idx] : 0.f;
-        if (!(x > 0.f)) x = 0.f;                   // negatives, -0.0 and NaN carry no mass
-        val[e] = x;
+        val[e] = ok ? sc[idx] : 0.f;
         if (ok) valid |= 1ull << e;
-        mx = fmaxf(mx, x);
+        mx = fmaxf(mx, mass_of(val[e]));
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
@@ -288,13 +289,13 @@ void top_p_kernel(const TopPParams p)
     mx = 0.f;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) mx = fmaxf(mx, s_redf[w]);
-    if (!(mx > 0.f) || !(mx < INFINITY)) { if (tid == 0) p.count[b] = 0; return; }
+    if (!(mx > 0.f)) { if (tid == 0) p.count[b] = 0; return; }
 
     // fixed point by an exact power-of-two scaling: the largest score lands in [2^39, 2^40)
     int mx_exp;
     (void)frexpf(mx, &mx_exp);
     const int fix_shift = 40 - mx_exp;
-    auto to_fix = [&](float x) { return (unsigned long long)ldexpf(x, fix_shift); };
+    auto to_fix = [&](float x) { return (unsigned long long)ldexpf(mass_of(x), fix_shift); };
     unsigned long long mine = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) mine += to_fix(val[e]);

@@ -65,7 +65,8 @@ def test_bad_arguments_are_rejected_before_any_launch(B):
     rc = lib.specvlm_score(null, 0, 0, null, 0, 0, null, null, null, 1, 4, 10, 8, 4, 12, 4, 2, 128, 0.1,
                            0, null, 0.0, null, null, 0, null)
     assert rc == -1
-    rc = lib.specvlm_gather_kv(null, null, 0, 0, 0, null, null, 0, 0, 0, 1, 10, 0, 4, null, 5, 2, 128, null)
+    rc = lib.specvlm_gather_kv(null, null, 0, 0, 0, null, null, 0, 0, 0, 1, 10, 0, 4, null, 5,
+                               null, null, null, 1, null, 2, 128, null)
     assert rc == -1
     # accept: gamma < 0, vocab < 1, draft logits without uniforms
     rc = lib.specvlm_accept(null, null, null, null, 1, -1, 10, 1.0, null, null, null, 0, null)

@@ -192,6 +192,32 @@ def test_score_full_size_72b_layer_two_head_groups(B):
     assert_scores_close(got, want, "72b-full, two live kv-head groups")
 
 
+@pytest.mark.parametrize("mode,live", [(0, (1, 6)), (1, (3,))])
+def test_score_full_size_32b_long_layer_live_head_groups(B, mode, live):
+    """The 32B long-video shape (256 text queries x 32 768 video keys, 40/8 heads: group 5, d 128), both
+    normalisation domains, in the launch configuration a full-size call gets.  As in the 72B test the
+    queries of the other kv-head groups are zeroed, which makes their rows uniform over the keys they are
+    normalised over: 1 / (visible keys) per column in mode 0, 1 / V in mode 1."""
+    w = synth.V32B_LONG
+    t = synth.make_layer(w)
+    q, k = t["q_text"].copy(), t["k"]
+    L, V, hq, hkv = w.n_text, w.n_video, w.n_q_heads, w.n_kv_heads
+    group = hq // hkv
+    for g in range(hkv):
+        if g not in live:
+            q[:, g * group:(g + 1) * group] = 0
+    pos0 = V
+    got = B.score(dev_bf16(q), dev_bf16(k[:V + L]), 0, V, pos0, w.softmax_scale, norm_mode=mode)
+    torch.cuda.synchronize()
+    want = np.zeros(V)
+    for g in live:
+        hs = slice(g * group, (g + 1) * group)
+        want += group * oracle.score(q[:, hs], k[:V + L, g:g + 1], 0, V, pos0, w.softmax_scale, norm_mode=mode)
+    uniform = np.mean([1.0 / (pos0 + i + 1) for i in range(L)]) if mode == 0 else 1.0 / V
+    want = (want + (hkv - len(live)) * group * uniform) / hq
+    assert_scores_close(got, want, f"32b-long mode {mode}, live kv-head groups {live}")
+
+
 def test_score_argument_errors(B):
     q = torch.zeros((4, 4, 64), dtype=torch.bfloat16, device="cuda")
     k = torch.zeros((20, 1, 64), dtype=torch.bfloat16, device="cuda")
@@ -263,6 +289,12 @@ def test_select_device_side_budget_errors(B):
     assert keep[2].item() == -1
     with pytest.raises(B.SpecVLMError):
         B.select(s, i32(1), i32(2), 200)                              # total_keep > tokens
+    # a request longer than the stated maximum is refused on the device and writes nothing
+    keep0 = torch.full((4,), -7, dtype=torch.int32, device="cuda")
+    _, _, st = B.select(s, i32(1), i32(4), 4, cu_video=i32([0, 100]), cu_keep=i32([0, 4]), max_n_video=50,
+                        want_status=True, keep_idx=keep0)
+    torch.cuda.synchronize()
+    assert st.item() == -1 and keep0.cpu().tolist() == [-7] * 4
 
 
 # ----------------------------------------------------------------- gather
@@ -296,6 +328,82 @@ def test_gather_head_major_source_and_destination(B):
         np.testing.assert_array_equal(host_bits(dst[l]), oracle.gather_kv(k[l], 0, V, keep))
 
 
+@pytest.mark.parametrize("name,layers,V,L,hkv,d,keeps", [
+    ("32b-long", 2, 32768, 256, 8, 128, (3277, 8192, 16384)),      # keep 10 / 25 / 50 % of 128 x 16 x 16 tokens
+    ("72b self-speculation", 2, 12544, 256, 8, 128, (1254,)),      # the verifier's own cache shape, keep 10 %
+])
+def test_gather_full_size_shapes(B, name, layers, V, L, hkv, d, keeps):
+    """Gather at the sizes the long-video and self-speculation configurations give it, with the kept
+    set that the selection produces for a long-tailed score vector (half top-k, half stride)."""
+    k, v = rnd_bits((layers, V + L, hkv, d), 190 + V), rnd_bits((layers, V + L, hkv, d), 191 + V)
+    kdv, vdv = dev_bf16(k), dev_bf16(v)
+    scores = synth.make_scores(V, 192)
+    for n_keep in keeps:
+        keep, _ = oracle.select(scores, n_keep // 2, n_keep)
+        kd, vd, st = B.gather_kv(kdv, vdv, 0, V, i32(keep), want_status=True)
+        torch.cuda.synchronize()
+        assert st.item() == 0
+        for l in range(layers):
+            np.testing.assert_array_equal(host_bits(kd[l]), oracle.gather_kv(k[l], 0, V, keep), err_msg=name)
+            np.testing.assert_array_equal(host_bits(vd[l]), oracle.gather_kv(v[l], 0, V, keep), err_msg=name)
+
+
+@pytest.mark.parametrize("hkv,d,P", [(2, 64, 0), (4, 128, 3), (3, 64, 2)])
+def test_gather_ragged_batch_in_one_launch(B, hkv, d, P):
+    """Several requests of different lengths in one launch (device prefix offsets), against the oracle's
+    gather of every request on its own; one request keeps nothing, one keeps everything."""
+    layers = 3
+    Vs = [700, 196, 1300, 64, 333]
+    Ls = [40, 70, 9, 0, 5]
+    n_keeps = [70, 0, 130, 64, 33]
+    rng = np.random.default_rng(93)
+    ks = [rnd_bits((layers, P + V + L, hkv, d), 500 + i) for i, (V, L) in enumerate(zip(Vs, Ls))]
+    vs = [rnd_bits((layers, P + V + L, hkv, d), 520 + i) for i, (V, L) in enumerate(zip(Vs, Ls))]
+    keeps = [np.sort(rng.choice(V, n, replace=False)).astype(np.int32) for V, n in zip(Vs, n_keeps)]
+    cu_keys = np.concatenate([[0], np.cumsum([P + V + L for V, L in zip(Vs, Ls)])])
+    cu_video = np.concatenate([[0], np.cumsum(Vs)])
+    cu_keep = np.concatenate([[0], np.cumsum(n_keeps)])
+    kd, vd, st = B.gather_kv(dev_bf16(np.concatenate(ks, axis=1)), dev_bf16(np.concatenate(vs, axis=1)), P,
+                             int(cu_video[-1]), i32(np.concatenate(keeps)), cu_keys=i32(cu_keys),
+                             cu_video=i32(cu_video), cu_keep=i32(cu_keep), want_status=True)
+    torch.cuda.synchronize()
+    assert st.item() == 0
+    o = 0
+    for i in range(len(Vs)):
+        n_dst = P + Ls[i] + n_keeps[i]
+        for l in range(layers):
+            np.testing.assert_array_equal(host_bits(kd[l, o:o + n_dst]), oracle.gather_kv(ks[i][l], P, Vs[i], keeps[i]))
+            np.testing.assert_array_equal(host_bits(vd[l, o:o + n_dst]), oracle.gather_kv(vs[i][l], P, Vs[i], keeps[i]))
+        o += n_dst
+    assert o == kd.shape[1]
+
+
+def test_gather_reports_indices_outside_the_video(B):
+    """An index outside its request's video span is reported through the status word; its destination
+    row is zero-filled, every other row is the plain copy, nothing outside the source is read."""
+    V, L, hkv, d = 300, 10, 2, 64
+    k = rnd_bits((1, V + L, hkv, d), 96)
+    keep = np.array([3, 50, 299, 300, 7], np.int32)          # 300 is one past the video
+    kd, _, st = B.gather_kv(dev_bf16(k), None, 0, V, i32(keep), want_status=True)
+    torch.cuda.synchronize()
+    assert st.item() == -1
+    got = host_bits(kd[0])
+    good = [0, 1, 2, 4]
+    want = oracle.gather_kv(k[0], 0, V, keep[good])
+    np.testing.assert_array_equal(got[good], want[:4])
+    assert not got[3].any()
+    np.testing.assert_array_equal(got[5:], want[4:])
+    kd, _, st = B.gather_kv(dev_bf16(k), None, 0, V, i32(np.array([-1, 5], np.int32)), want_status=True)
+    torch.cuda.synchronize()
+    assert st.item() == -1 and not host_bits(kd[0])[0].any()
+    # a batch whose device-side sizes do not fit together (request 1 keeps more than its video holds)
+    kd, _, st = B.gather_kv(dev_bf16(k), None, 0, 200, i32(np.arange(60, dtype=np.int32)),
+                            cu_keys=i32([0, 160, 310]), cu_video=i32([0, 150, 200]), cu_keep=i32([0, 5, 60]),
+                            want_status=True)
+    torch.cuda.synchronize()
+    assert st.item() == -1
+
+
 def test_attention_over_gathered_cache(B):
     """The draft's decode over the gathered cache equals the oracle's attention
     over the oracle's gather (the path select -> gather -> draft attention)."""
@@ -324,12 +432,14 @@ def test_top_p_count_matches_oracle(B, V, seed, levels):
     sd = torch.from_numpy(s).cuda()
     checked = 0
     for lam in (0.0, 0.05, 0.1, 0.4, 0.5, 0.9, 1.0):
+        lam = float(np.float32(lam))                  # the ABI takes lambda as fp32: both sides see that value
         want, margin = oracle.top_p_count(s, lam, want_margin=True)
         got = B.top_p_count(sd, lam)
         torch.cuda.synchronize()
         if lam == 1.0:
-            # fp32-exact fixed point vs fp64: the full sum is reached at the last positive score
-            assert got.item() <= V and got.item() >= want - 1 - (s == 0).sum()
+            # these scores span < 2^16, so the fp64 sums and the 2^-40 fixed point are both exact:
+            # the whole mass is reached exactly at the last positive score
+            assert got.item() == want == int((s > 0).sum())
             continue
         if margin > 1e-6:
             assert got.item() == want, (lam, got.item(), want, margin)
@@ -337,6 +447,34 @@ def test_top_p_count_matches_oracle(B, V, seed, levels):
         else:
             assert abs(got.item() - want) <= 1
     assert checked >= 4
+
+
+def test_top_p_count_values_without_mass(B):
+    """Negative, zero, NaN and infinite scores add no mass on either side and keep their rank."""
+    hand = np.array([0.5, -1.0, 0.25, np.nan, 0.25, 0.0, -0.0], np.float32)
+    for lam, want in ((0.0, 0), (0.5, 1), (0.6, 2), (0.75, 2), (0.76, 3), (1.0, 3)):
+        assert oracle.top_p_count(hand, float(np.float32(lam))) == want
+        assert B.top_p_count(torch.from_numpy(hand).cuda(), lam).item() == want, lam
+    inf = np.array([1.0, np.inf, 1.0], np.float32)
+    for lam, want in ((0.5, 2), (1.0, 3)):
+        assert B.top_p_count(torch.from_numpy(inf).cuda(), lam).item() == want == oracle.top_p_count(inf, lam)
+    assert B.top_p_count(torch.tensor([-1.0, float("nan"), 0.0]).cuda(), 0.7).item() == 0
+    # long-tailed scores with a fifth of the entries replaced by values without mass
+    for V, seed in ((12544, 0), (32768, 1), (3000, 2)):
+        s = synth.make_scores(V, 470 + seed)
+        rng = np.random.default_rng(seed)
+        junk = rng.choice(V, V // 5, replace=False)
+        s[junk] = rng.choice(np.array([-1.0, 0.0, -0.0, np.nan, -np.inf, np.inf, -3e-5], np.float32), junk.size)
+        sd = torch.from_numpy(s).cuda()
+        checked = 0
+        for lam in (0.05, 0.4, 0.5, 0.9, 1.0):
+            lam = float(np.float32(lam))
+            want, margin = oracle.top_p_count(s, lam, want_margin=True)
+            got = B.top_p_count(sd, lam).item()
+            if margin > 1e-6 or lam == 1.0:
+                assert got == want, (V, lam, got, want, margin)
+                checked += 1
+        assert checked >= 3
 
 
 def test_top_p_count_batch_clamp_and_chain_to_select(B):
