@@ -244,6 +244,31 @@ int specvlm_decode_attn(
     void* workspace, size_t workspace_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * specvlm_decode_attn_static -- specvlm_decode_attn for callers that cannot
+ * allocate device memory or hand over a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as specvlm_decode_attn without the workspace pair; the
+ * split-K partial results live in an array inside the library's device image
+ * (specvlm_decode_attn_static_scratch_bytes() = 16 MiB, held by every GPU that
+ * loads the library until the process ends).  The call allocates nothing and
+ * frees nothing.
+ *   - A shape whose specvlm_decode_attn_workspace_bytes exceeds that size
+ *     returns SPECVLM_EWORKSPACE and launches nothing.
+ *   - All calls on one GPU share the array: calls must be ordered on one
+ *     stream (or otherwise not overlap); overlapping calls race.  The array
+ *     keeps the previous call's contents; the kernels never read a slot they
+ *     have not written in the same call.
+ * -------------------------------------------------------------------------- */
+size_t specvlm_decode_attn_static_scratch_bytes(void);
+
+int specvlm_decode_attn_static(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    void* out, float* lse, int num_splits, void* stream);
+
+/* --------------------------------------------------------------------------
  * specvlm_tree_attn -- specvlm_decode_attn for a block of draft-TREE nodes
  * (Sec. 3.2 "Bonus" and App. B: the tree is verified in one target forward
  * through a specialised attention mask).  Same arguments as specvlm_decode_attn

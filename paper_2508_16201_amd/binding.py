@@ -25,6 +25,7 @@ EXPORTS = (
     "specvlm_top_p_count_workspace_bytes", "specvlm_top_p_count",
     "specvlm_gather_kv",
     "specvlm_decode_attn_workspace_bytes", "specvlm_decode_attn",
+    "specvlm_decode_attn_static_scratch_bytes", "specvlm_decode_attn_static",
     "specvlm_accept_workspace_bytes", "specvlm_accept",
     "specvlm_tree_attn", "specvlm_accept_tree_workspace_bytes", "specvlm_accept_tree",
     "specvlm_baseline_count", "specvlm_baseline_workspace_bytes", "specvlm_baseline_keep",
@@ -66,6 +67,9 @@ def lib() -> C.CDLL:
         l.specvlm_decode_attn_workspace_bytes.argtypes = [i32] * 7
         l.specvlm_decode_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
                                           i32, i32, i32, f32, vp, vp, i32, vp, sz, vp]
+        l.specvlm_decode_attn_static_scratch_bytes.argtypes = []
+        l.specvlm_decode_attn_static.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
+                                                 i32, i32, i32, f32, vp, vp, i32, vp]
         l.specvlm_tree_attn.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32, i32, i32,
                                         i32, i32, i32, f32, vp, vp, vp, i32, vp, sz, vp]
         l.specvlm_accept_tree_workspace_bytes.argtypes = [i32] * 3
@@ -78,7 +82,7 @@ def lib() -> C.CDLL:
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
         for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
-                     "specvlm_decode_attn", "specvlm_accept", "specvlm_tree_attn",
+                     "specvlm_decode_attn", "specvlm_decode_attn_static", "specvlm_accept", "specvlm_tree_attn",
                      "specvlm_accept_tree"):
             getattr(l, name).restype = C.c_int
         _lib = l
@@ -300,6 +304,32 @@ def decode_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale
                                      num_splits, _ptr(workspace), workspace.numel(), _stream())
         _check("specvlm_tree_attn", rc)
     return (out, lse) if want_lse else out
+
+
+def decode_attn_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale: float, *,
+                       out: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                       cu_q: Optional[torch.Tensor] = None, cu_kv: Optional[torch.Tensor] = None,
+                       max_q_len: Optional[int] = None, max_kv_len: Optional[int] = None,
+                       num_splits: int = 0) -> torch.Tensor:
+    """decode_attn through the entry point that takes no workspace; the caller supplies every output
+    (this wrapper allocates nothing either)."""
+    tq, hq, d = q.shape
+    tk, hkv, _ = k.shape
+    if cu_q is None:
+        batch, q_len, kv_len = 1, tq, tk
+    else:
+        batch = cu_q.numel() - 1
+        if max_q_len is None or max_kv_len is None:
+            raise ValueError("max_q_len and max_kv_len are required with cu_q/cu_kv")
+        q_len, kv_len = max_q_len, max_kv_len
+    if out.stride() != q.stride() or v.stride() != k.stride():
+        raise ValueError("out must share q's strides, V must share K's")
+    qs, ks = _thd(q), _thd(k)
+    rc = lib().specvlm_decode_attn_static(_ptr(q), qs[0], qs[1], _ptr(k), _ptr(v), ks[0], ks[1],
+                                          _ptr(cu_q), _ptr(cu_kv), batch, q_len, kv_len, hq, hkv, d,
+                                          float(softmax_scale), _ptr(out), _ptr(lse), num_splits, _stream())
+    _check("specvlm_decode_attn_static", rc)
+    return out
 
 
 def tree_attn(q, k, v, softmax_scale, ancestor_mask: torch.Tensor, **kw):

@@ -878,6 +878,51 @@ extern "C" int specvlm_decode_attn(
                      out, lse, num_splits, workspace, workspace_bytes, stream);
 }
 
+// ---- the variant that takes no workspace ----
+// Scratch for callers that cannot allocate or pass one (code under HIP graph capture, serving loops
+// that own no spare device memory).  Every device that loads the library holds its own copy of this
+// array until the process ends; the name below is a host-side handle, the device address is looked
+// up once per device.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECVLM_ELAUNCH;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SPECVLM_ELAUNCH;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // (every thread looks up the same address)
+    }
+    *out = ptr;
+    return SPECVLM_OK;
+}
+
+extern "C" size_t specvlm_decode_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int specvlm_decode_attn_static(
+    const void* q, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
+    const int32_t* cu_q, const int32_t* cu_kv, int batch, int q_len, int kv_len,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    void* out, float* lse, int num_splits, void* stream)
+{
+    // the shape decides how much scratch the kernels use; a shape the array cannot hold is refused
+    // (a shape the workspace query itself rejects, size 0, is left to the argument checks below)
+    const size_t need = specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads, n_kv_heads,
+                                                            head_dim, num_splits);
+    if (need > kStaticScratchBytes) return SPECVLM_EWORKSPACE;
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != SPECVLM_OK) return rc;
+    return attn_impl(q, q_tok_stride, q_head_stride, k, v, kv_tok_stride, kv_head_stride, cu_q, cu_kv,
+                     batch, q_len, kv_len, n_q_heads, n_kv_heads, head_dim, softmax_scale, nullptr,
+                     out, lse, num_splits, ptr, kStaticScratchBytes, stream);
+}
+
 extern "C" int specvlm_tree_attn(
     const void* q, int64_t q_tok_stride, int64_t q_head_stride,
     const void* k, const void* v, int64_t kv_tok_stride, int64_t kv_head_stride,
