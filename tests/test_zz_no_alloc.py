@@ -28,10 +28,11 @@ def _case(B, q_len, kv_len, hq, hkv, d, seed, num_splits=0):
     out = torch.full_like(qd, float("nan"))
     lse = torch.full((q_len, hq), float("nan"), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # torch's allocator counts every allocation it serves: the call must add none
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     B.decode_attn_static(qd, kd, vd, scale, out=out, lse=lse, num_splits=num_splits)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     # the same kernels on the same inputs: bitwise equal to the workspace entry point
     assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
     assert torch.equal(lse, ref_lse)
