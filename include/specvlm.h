@@ -382,6 +382,19 @@ int specvlm_baseline_keep(
     int keep_budget, int stride_h, int stride_w, uint64_t seed,
     int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* stream);
 
+/* --------------------------------------------------------------------------
+ * specvlm_probe_read -- diagnostic, not a step of the method: one launch that
+ * merely reads `bytes_a` bytes at `a` and `bytes_b` bytes at `b` (device
+ * pointers, 16-byte aligned, sizes multiples of 16; either may be empty) with
+ * 2048 workgroups of plain 16-byte loads.  The benchmark times it over a
+ * layer's K and V to print what a bare read of the same bytes costs on the
+ * machine at hand, beside the attention kernel's time (Sec. 2.1: decoding is
+ * bound by moving the KV cache).  `sink` (device, 4 bytes, may be NULL) is
+ * never written in practice.
+ * -------------------------------------------------------------------------- */
+int specvlm_probe_read(const void* a, size_t bytes_a, const void* b, size_t bytes_b,
+                       void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTS = (
     "specvlm_accept_workspace_bytes", "specvlm_accept",
     "specvlm_tree_attn", "specvlm_accept_tree_workspace_bytes", "specvlm_accept_tree",
     "specvlm_baseline_count", "specvlm_baseline_workspace_bytes", "specvlm_baseline_keep",
+    "specvlm_probe_read",
 )
 
 
@@ -79,6 +80,8 @@ def lib() -> C.CDLL:
         l.specvlm_baseline_workspace_bytes.argtypes = [i32] * 2
         l.specvlm_baseline_keep.argtypes = [i32] * 8 + [C.c_uint64, vp, vp, sz, vp]
         l.specvlm_baseline_keep.restype = C.c_int
+        l.specvlm_probe_read.argtypes = [vp, sz, vp, sz, vp, vp]
+        l.specvlm_probe_read.restype = C.c_int
         l.specvlm_accept_workspace_bytes.argtypes = [i32] * 4
         l.specvlm_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
         for name in ("specvlm_score", "specvlm_select", "specvlm_top_p_count", "specvlm_gather_kv",
@@ -409,3 +412,16 @@ def baseline_keep(mode: str, n_video: int, keep_budget: int, *, n_frames: int = 
                                      workspace.numel() if workspace is not None else 0, _stream())
     _check("specvlm_baseline_keep", rc)
     return keep_idx
+
+
+# ------------------------------------------------------------------------ diagnostics
+def probe_read(a: torch.Tensor, b: Optional[torch.Tensor] = None) -> None:
+    """One launch that merely reads the bytes of `a` (and `b`): the bare-read yardstick of the benchmark.
+    Both must be dense in memory (any dimension order)."""
+    def span(t):
+        if t is None:
+            return None, 0
+        return C.c_void_p(t.data_ptr()), t.numel() * t.element_size()
+    pa, na = span(a)
+    pb, nb = span(b)
+    _check("specvlm_probe_read", lib().specvlm_probe_read(pa, na, pb, nb, None, _stream()))
