@@ -86,16 +86,19 @@ int specvlm_version(void);
  *   scores   fp32 [n_video]:  scores = beta * scores + (1/(H_q n_text)) sum_{h,i} G
  *            (beta = 0 overwrites and never reads the old contents)
  *
- * A batch: the requests are concatenated along the token axis of q_text,
- * k_cache, row_lse and scores, and cu_text, cu_keys, cu_video are HOST int32
- * arrays of batch+1 prefix offsets (unlike the other calls' device arrays: the
- * split plan of every request is made on the host, and scoring happens at
- * prefill, when the host knows the lengths).  n_text, n_keys, n_video are then
- * the maxima over the batch; video_start applies inside every request;
- * text_pos0 = -1 places each request's text queries on its last n_text_b keys
- * (text_pos0 >= 0 is the same position for every request).  The requests are
- * enqueued one after the other and share the workspace; every request is
- * validated before the first launch.  With all three NULL, batch must be 1.
+ * A batch (one set of launches for all requests): the requests are
+ * concatenated along the token axis of q_text, k_cache, row_lse and scores, and
+ * cu_text, cu_keys, cu_video are DEVICE int32 arrays of batch+1 prefix offsets,
+ * as in every other call.  n_text, n_keys, n_video are then the maxima over the
+ * batch (host ints: they size the launches and the workspace; the split plan is
+ * made from them and a request's workgroups find their real sizes on the
+ * device); video_start applies inside every request; text_pos0 = -1 places each
+ * request's text queries on its last n_text_b keys (text_pos0 >= 0 is the same
+ * position for every request).  A request whose device-side sizes exceed the
+ * maxima or do not fit together (video_start + n_video_b > n_keys_b) is skipped:
+ * its scores are left untouched.  With all three NULL, batch must be 1 and
+ * text_pos0 = -1 means n_keys - n_text.
+ * The workspace query takes the batch and the same maxima.
  * -------------------------------------------------------------------------- */
 size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_keys, int n_video,
                                      int n_q_heads, int n_kv_heads, int head_dim,

@@ -142,34 +142,44 @@ def score_workspace_bytes(n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_d
                                                head_dim, int(have_row_lse))
 
 
-def _host_i32(a):
-    """Host int32 prefix offsets for specvlm_score (which plans every request on the host)."""
+def _dev_i32(a, device):
+    """Device int32 prefix offsets; a host sequence is uploaded (and its maxima returned)."""
+    if isinstance(a, torch.Tensor):
+        return a, None
     arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
-    return arr, arr.ctypes.data_as(C.c_void_p)
+    return torch.from_numpy(arr).to(device), arr
 
 
 def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
           text_pos0: int, softmax_scale: float, *, norm_mode: int = 0,
           row_lse: Optional[torch.Tensor] = None, beta: float = 0.0,
           scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-          cu_text=None, cu_keys=None, cu_video=None) -> torch.Tensor:
+          cu_text=None, cu_keys=None, cu_video=None, max_n_text: Optional[int] = None,
+          max_n_keys: Optional[int] = None, max_n_video: Optional[int] = None,
+          total_video: Optional[int] = None) -> torch.Tensor:
     """q_text [L,H_q,d] bf16, k_cache [n_keys,H_kv,d] bf16 -> scores fp32 [n_video].
 
-    A batch: requests concatenated along the token axis, cu_text / cu_keys / cu_video = HOST int32
-    prefix offsets [batch+1]; n_video is then ignored (taken from cu_video) and text_pos0 = -1 places
-    every request's text queries on its last keys."""
+    A batch: requests concatenated along the token axis, cu_text / cu_keys / cu_video = int32 prefix
+    offsets [batch+1] on the device (host sequences are uploaded); n_video is then ignored and
+    text_pos0 = -1 places every request's text queries on its last keys.  With device tensors the
+    maxima over the batch and the total number of video tokens must be given."""
     n_text, hq, d = q_text.shape
     n_keys, hkv, _ = k_cache.shape
-    batch, ptrs, keep_alive = 1, (None, None, None), []
+    batch, ptrs = 1, (None, None, None)
     if cu_text is not None:
-        hosts = [_host_i32(a) for a in (cu_text, cu_keys, cu_video)]
-        keep_alive = [h[0] for h in hosts]
-        ptrs = tuple(h[1] for h in hosts)
-        batch = len(keep_alive[0]) - 1
-        total_video = int(keep_alive[2][-1])
-        n_text = int(np.diff(keep_alive[0]).max()) if batch else 0
-        n_keys = int(np.diff(keep_alive[1]).max()) if batch else 0
-        n_video = int(np.diff(keep_alive[2]).max()) if batch else 0
+        dev = [_dev_i32(a, q_text.device) for a in (cu_text, cu_keys, cu_video)]
+        ptrs = tuple(x[0] for x in dev)
+        batch = ptrs[0].numel() - 1
+        hosts = [x[1] for x in dev]
+        if all(h is not None for h in hosts):
+            n_text = int(np.diff(hosts[0]).max()) if batch else 0
+            n_keys = int(np.diff(hosts[1]).max()) if batch else 0
+            n_video = int(np.diff(hosts[2]).max()) if batch else 0
+            total_video = int(hosts[2][-1])
+        else:
+            if None in (max_n_text, max_n_keys, max_n_video, total_video):
+                raise ValueError("device cu arrays need max_n_text, max_n_keys, max_n_video and total_video")
+            n_text, n_keys, n_video = max_n_text, max_n_keys, max_n_video
     else:
         total_video = n_video
     if scores is None:
@@ -180,8 +190,8 @@ def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video
     workspace = _ws(workspace, need, q_text)
     qs, ks = _thd(q_text), _thd(k_cache)
     rc = lib().specvlm_score(_ptr(q_text), qs[0], qs[1], _ptr(k_cache), ks[0], ks[1],
-                             ptrs[0], ptrs[1], ptrs[2], batch, n_text, n_keys, video_start, n_video, text_pos0,
-                             hq, hkv, d, float(softmax_scale), norm_mode, _ptr(row_lse),
+                             _ptr(ptrs[0]), _ptr(ptrs[1]), _ptr(ptrs[2]), batch, n_text, n_keys, video_start,
+                             n_video, text_pos0, hq, hkv, d, float(softmax_scale), norm_mode, _ptr(row_lse),
                              float(beta), _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
     _check("specvlm_score", rc)
     return scores

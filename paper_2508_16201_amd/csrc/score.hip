@@ -69,7 +69,43 @@ struct ScoreParams {
     float* part_cols;              // [H_kv][b_splits][video_pad]
     float beta, inv_count;
     float* scores;
+    // a batch: device prefix offsets of the requests (null: one request, the scalars above are its sizes;
+    // else the scalars are the maxima over the batch and the sizes of a request come from here)
+    const int32_t* cu_text;
+    const int32_t* cu_keys;
+    const int32_t* cu_video;
+    int batch, norm_mode;
+    int64_t ws_ml, ws_lse, ws_cols;    // floats per request in part_ml / lse2 / part_cols
 };
+
+// Request b's view of the launch parameters: pointers moved to its rows, sizes and positions its
+// own.  The plan (padding, split sizes) stays that of the maxima, so a workgroup whose share lies
+// beyond the request's real size finds an empty range.  Returns false for a request whose sizes do
+// not fit the maxima or each other: every kernel skips it.
+__device__ __forceinline__ bool score_select_request(ScoreParams& p, int b)
+{
+    p.part_ml += (int64_t)b * p.ws_ml;
+    p.lse2 += (int64_t)b * p.ws_lse;
+    p.part_cols += (int64_t)b * p.ws_cols;
+    if (!p.cu_text) return true;
+    const int t0 = p.cu_text[b], k0 = p.cu_keys[b], v0 = p.cu_video[b];
+    const int nt = p.cu_text[b + 1] - t0, nk = p.cu_keys[b + 1] - k0, nv = p.cu_video[b + 1] - v0;
+    if (nt < 0 || nk < 0 || nv < 0 || nt > p.n_text || nk > p.n_keys || nv > p.n_video ||
+        p.video_start + nv > nk)
+        return false;
+    const int pos0 = p.text_pos0 >= 0 ? p.text_pos0 : nk - nt;      // -1: the text queries are the last keys
+    if (pos0 < 0) return false;
+    p.q += (int64_t)t0 * p.q_tok;
+    p.k += (int64_t)k0 * p.k_tok;
+    if (p.row_lse) p.row_lse += (int64_t)t0 * p.n_q_heads;
+    p.scores += v0;
+    p.n_text = nt; p.n_keys = nk; p.n_video = nv; p.text_pos0 = pos0;
+    p.key_lo = p.norm_mode ? p.video_start : 0;
+    p.key_hi = p.norm_mode ? p.video_start + nv : nk;
+    p.b_needs_mask = (p.video_start + nv - 1 > pos0) ? 1 : 0;
+    p.inv_count = nt > 0 ? 1.f / ((float)p.n_q_heads * (float)nt) : 0.f;
+    return true;
+}
 
 constexpr int score_vmcnt_imm(int n)
 {
@@ -134,8 +170,9 @@ __device__ __forceinline__ void score_rows_max(floatx4 (&acc)[4], bool mask, int
 
 template <int D, int MODE>
 __global__ __launch_bounds__(256)
-void score_sweep_kernel(const ScoreParams p)
+void score_sweep_kernel(const ScoreParams p_launch)
 {
+    ScoreParams p = p_launch;
     constexpr int KK = D / 32;
     constexpr int CH = D / 8;                        // 16-byte chunks per vector
     constexpr int ROW_BYTES = D * 2;
@@ -160,16 +197,17 @@ void score_sweep_kernel(const ScoreParams p)
     const int n_blocks = (MODE == 0 ? p.rows_pad : p.video_pad) / kScoreBlock;
     const int n_split = (MODE == 0 ? p.a_splits : p.b_splits);
     const int vid = xcd_logical_id(blockIdx.x, gridDim.x);
-    if (vid >= n_blocks * n_split * p.n_kv_heads) return;
+    if (vid >= n_blocks * n_split * p.n_kv_heads * p.batch) return;
     const int blk = vid % n_blocks;
     const int split = (vid / n_blocks) % n_split;
-    const int g = vid / (n_blocks * n_split);
+    const int g = (vid / (n_blocks * n_split)) % p.n_kv_heads;
+    if (!score_select_request(p, vid / (n_blocks * n_split * p.n_kv_heads))) return;
     const int stat0 = blk * kScoreBlock + wave * 64;             // this wave's first stationary vector
 
     // streamed range of this workgroup (multiples of the tile size)
     int s_begin, s_end;
     if (MODE == 0) {
-        s_begin = p.key_lo + split * p.a_split_keys;
+        s_begin = min(p.key_hi, p.key_lo + split * p.a_split_keys);
         s_end = min(p.key_hi, s_begin + p.a_split_keys);
     } else {
         s_begin = split * p.b_split_rows;
@@ -427,10 +465,12 @@ void score_sweep_kernel(const ScoreParams p)
 
 // lse2[g][row] from the pass-A partials, or from the caller's natural-log values.
 __global__ __launch_bounds__(256)
-void score_lse_kernel(const ScoreParams p)
+void score_lse_kernel(const ScoreParams p_launch)
 {
+    ScoreParams p = p_launch;
     const int row = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
     if (row >= p.rows_pad) return;
+    if (!score_select_request(p, blockIdx.z)) return;
     float out = INFINITY;                       // padded / keyless rows contribute nothing
     const int gl = row / p.l_pad, i = row % p.l_pad;
     if (row < p.rows && i < p.n_text) {
@@ -460,8 +500,10 @@ void score_lse_kernel(const ScoreParams p)
 }
 
 __global__ __launch_bounds__(256)
-void score_final_kernel(const ScoreParams p)
+void score_final_kernel(const ScoreParams p_launch)
 {
+    ScoreParams p = p_launch;
+    if (!score_select_request(p, blockIdx.y)) return;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= p.n_video) return;
     float a = 0.f;
@@ -484,7 +526,7 @@ struct ScorePlan {
     size_t off_ml, off_lse, off_cols, total;
 };
 
-static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video, int n_q_heads,
+static ScorePlan score_plan(int batch, int n_text, int n_keys, int video_start, int n_video, int n_q_heads,
                             int n_kv_heads, int head_dim, int norm_mode, int have_row_lse)
 {
     ScorePlan s;
@@ -519,9 +561,9 @@ static ScorePlan score_plan(int n_text, int n_keys, int video_start, int n_video
         return best;
     };
     const int dom = s.key_hi - s.key_lo;
-    const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads;
+    const int blocks_a = (s.rows_pad / kScoreBlock) * n_kv_heads * batch;
     s.a_splits = best_splits(blocks_a, dom, kMaxSplitsA, &s.a_split_keys);
-    const int blocks_b = (s.video_pad / kScoreBlock) * n_kv_heads;
+    const int blocks_b = (s.video_pad / kScoreBlock) * n_kv_heads * batch;
     s.b_splits = best_splits(blocks_b, s.rows, kMaxSplitsB, &s.b_split_rows);
     size_t off = 0;
     s.off_ml = off;
@@ -543,81 +585,11 @@ extern "C" size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_key
     if (batch < 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
         n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
         return 0;
-    if (batch > 1) {
-        // The requests of a batch are scored one after the other in the same workspace, each with
-        // the split plan of its own sizes; the arguments are the maxima over the batch.  Bound every
-        // plan: at most kMaxSplitsA key splits and kMaxSplitsB row splits, rows and columns padded.
-        const int group = n_q_heads / n_kv_heads;
-        const size_t rows_pad = (size_t)round_up(group * round_up(n_text > 0 ? n_text : 1, kScoreTile), kScoreBlock);
-        const size_t video_pad = (size_t)round_up(n_video > 0 ? n_video : 1, kScoreBlock);
-        size_t total = align256((size_t)n_kv_heads * rows_pad * sizeof(float)) +
-                       align256((size_t)n_kv_heads * kMaxSplitsB * video_pad * sizeof(float));
-        if (!have_row_lse) total += align256((size_t)n_kv_heads * rows_pad * kMaxSplitsA * 2 * sizeof(float));
-        return total;
-    }
-    // the split plan depends on the normalisation domain; size for the larger one
-    const ScorePlan a = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
-    const ScorePlan b = score_plan(n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
-    return a.total > b.total ? a.total : b.total;
-}
-
-// One request: validation without side effects (launch == false), or the launches.
-static int score_one(
-    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
-    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
-    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
-    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
-    int norm_mode, const float* row_lse, float beta, float* scores,
-    void* workspace, size_t workspace_bytes, void* stream, bool launch)
-{
-    if (n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0 || text_pos0 < 0) return SPECVLM_EINVAL;
-    if ((int64_t)video_start + n_video > n_keys) return SPECVLM_EINVAL;
-    if (n_video == 0) return SPECVLM_OK;
-    if (!scores) return SPECVLM_EINVAL;
-    if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
-    if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
-
-    const ScorePlan plan = score_plan(n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
-                                      head_dim, norm_mode, row_lse != nullptr);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.total) return SPECVLM_EWORKSPACE;
-    if (!launch) return SPECVLM_OK;
-    ScoreParams p;
-    p.q = (const __bf16*)q_text; p.k = (const __bf16*)k_cache;
-    p.q_tok = q_tok_stride; p.q_head = q_head_stride; p.k_tok = k_tok_stride; p.k_head = k_head_stride;
-    p.n_text = n_text; p.n_keys = n_keys; p.video_start = video_start; p.n_video = n_video;
-    p.text_pos0 = text_pos0;
-    p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = n_q_heads / n_kv_heads;
-    p.scale_log2 = softmax_scale * kLog2e;
-    p.l_pad = plan.l_pad;
-    p.rows = plan.rows; p.rows_pad = plan.rows_pad; p.video_pad = plan.video_pad;
-    p.key_lo = plan.key_lo; p.key_hi = plan.key_hi;
-    p.a_splits = plan.a_splits; p.a_split_keys = plan.a_split_keys;
-    p.b_splits = plan.b_splits; p.b_split_rows = plan.b_split_rows;
-    p.b_needs_mask = (video_start + n_video - 1 > text_pos0) ? 1 : 0;
-    p.part_ml = (float*)((char*)workspace + plan.off_ml);
-    p.lse2 = (float*)((char*)workspace + plan.off_lse);
-    p.row_lse = row_lse;
-    p.part_cols = (float*)((char*)workspace + plan.off_cols);
-    p.beta = beta;
-    p.inv_count = (n_text > 0) ? 1.f / ((float)n_q_heads * (float)n_text) : 0.f;
-    p.scores = scores;
-    hipStream_t s = (hipStream_t)stream;
-
-    if (n_text > 0) {
-        if (!row_lse && p.key_hi > p.key_lo) {
-            dim3 grid(round_up((plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits, kNumXcd));
-            if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 0>), grid, dim3(256), 0, s, p);
-            else                 hipLaunchKernelGGL((score_sweep_kernel<64, 0>), grid, dim3(256), 0, s, p);
-        }
-        hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads), dim3(256), 0, s, p);
-        dim3 grid(round_up((plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits, kNumXcd));
-        if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 1>), grid, dim3(256), 0, s, p);
-        else                 hipLaunchKernelGGL((score_sweep_kernel<64, 1>), grid, dim3(256), 0, s, p);
-    } else {
-        p.b_splits = 0;          // no language queries: the mean is empty, only beta applies
-    }
-    hipLaunchKernelGGL(score_final_kernel, dim3((n_video + 255) / 256), dim3(256), 0, s, p);
-    return launch_status();
+    // every request of a batch has its own slice, sized by the plan of the maxima; the split plan
+    // depends on the normalisation domain: size for the larger one
+    const ScorePlan a = score_plan(batch, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
+    const ScorePlan b = score_plan(batch, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
+    return (size_t)batch * (a.total > b.total ? a.total : b.total);
 }
 
 extern "C" int specvlm_score(
@@ -642,27 +614,67 @@ extern "C" int specvlm_score(
     const bool ragged = cu_text || cu_keys || cu_video;
     if (ragged && !(cu_text && cu_keys && cu_video)) return SPECVLM_EINVAL;
     if (!ragged && batch != 1) return SPECVLM_EINVAL;
-    // Two passes over the requests: every request is validated (sizes, workspace) before the first
-    // launch, so a failed call has enqueued nothing.  The requests run one after the other on the
-    // stream and share the workspace.
-    for (int pass = 0; pass < 2; ++pass) {
-        for (int b = 0; b < batch; ++b) {
-            int nt = n_text, nk = n_keys, nv = n_video;
-            int64_t t0 = 0, k0 = 0, v0 = 0;
-            if (ragged) {
-                t0 = cu_text[b]; k0 = cu_keys[b]; v0 = cu_video[b];
-                nt = cu_text[b + 1] - cu_text[b]; nk = cu_keys[b + 1] - cu_keys[b]; nv = cu_video[b + 1] - cu_video[b];
-                if (nt > n_text || nk > n_keys || nv > n_video) return SPECVLM_EINVAL;   // the scalars are the maxima
-            }
-            const int pos0 = text_pos0 >= 0 ? text_pos0 : nk - nt;     // -1: the text queries are the last keys
-            const int rc = score_one(
-                (const __bf16*)q_text + t0 * q_tok_stride, q_tok_stride, q_head_stride,
-                (const __bf16*)k_cache + k0 * k_tok_stride, k_tok_stride, k_head_stride,
-                nt, nk, video_start, nv, pos0, n_q_heads, n_kv_heads, head_dim, softmax_scale, norm_mode,
-                row_lse ? row_lse + t0 * n_q_heads : nullptr, beta, scores ? scores + v0 : nullptr,
-                workspace, workspace_bytes, stream, pass == 1);
-            if (rc != SPECVLM_OK) return rc;
-        }
+    if (batch > 65535) return SPECVLM_EUNSUPPORTED;
+    if (n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0) return SPECVLM_EINVAL;
+    if ((int64_t)video_start + n_video > n_keys) return SPECVLM_EINVAL;
+    if (!ragged) {
+        if (text_pos0 < 0) text_pos0 = n_keys - n_text;       // -1: the text queries are the last keys
+        if (text_pos0 < 0) return SPECVLM_EINVAL;
     }
-    return SPECVLM_OK;
+    if (n_video == 0) return SPECVLM_OK;
+    if (!scores) return SPECVLM_EINVAL;
+    if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
+    if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
+
+    // One plan for the whole batch, made from the maxima (the host does not know the requests' own
+    // sizes); a request's kernels find their real sizes in the cu arrays on the device.
+    const ScorePlan plan = score_plan(batch, n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
+                                      head_dim, norm_mode, row_lse != nullptr);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (size_t)batch * plan.total)
+        return SPECVLM_EWORKSPACE;
+    ScoreParams p;
+    p.q = (const __bf16*)q_text; p.k = (const __bf16*)k_cache;
+    p.q_tok = q_tok_stride; p.q_head = q_head_stride; p.k_tok = k_tok_stride; p.k_head = k_head_stride;
+    p.n_text = n_text; p.n_keys = n_keys; p.video_start = video_start; p.n_video = n_video;
+    p.text_pos0 = text_pos0;
+    p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = n_q_heads / n_kv_heads;
+    p.scale_log2 = softmax_scale * kLog2e;
+    p.l_pad = plan.l_pad;
+    p.rows = plan.rows; p.rows_pad = plan.rows_pad; p.video_pad = plan.video_pad;
+    p.key_lo = plan.key_lo; p.key_hi = plan.key_hi;
+    p.a_splits = plan.a_splits; p.a_split_keys = plan.a_split_keys;
+    p.b_splits = plan.b_splits; p.b_split_rows = plan.b_split_rows;
+    p.b_needs_mask = (video_start + n_video - 1 > text_pos0) ? 1 : 0;
+    // workspace: [batch] slices of each of the three arrays
+    const size_t n_ml = row_lse ? 0 : (size_t)n_kv_heads * plan.rows_pad * plan.a_splits * 2;
+    const size_t n_lse = (size_t)n_kv_heads * plan.rows_pad;
+    const size_t n_cols = (size_t)n_kv_heads * plan.b_splits * plan.video_pad;
+    char* ws = (char*)workspace;
+    p.part_ml = (float*)ws;  ws += align256(batch * n_ml * sizeof(float));
+    p.lse2 = (float*)ws;     ws += align256(batch * n_lse * sizeof(float));
+    p.part_cols = (float*)ws;
+    p.ws_ml = (int64_t)n_ml; p.ws_lse = (int64_t)n_lse; p.ws_cols = (int64_t)n_cols;
+    p.row_lse = row_lse;
+    p.beta = beta;
+    p.inv_count = (n_text > 0) ? 1.f / ((float)n_q_heads * (float)n_text) : 0.f;
+    p.scores = scores;
+    p.cu_text = cu_text; p.cu_keys = cu_keys; p.cu_video = cu_video;
+    p.batch = batch; p.norm_mode = norm_mode;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (n_text > 0) {
+        if (!row_lse && p.key_hi > p.key_lo) {
+            dim3 grid(round_up((plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits * batch, kNumXcd));
+            if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 0>), grid, dim3(256), 0, s, p);
+            else                 hipLaunchKernelGGL((score_sweep_kernel<64, 0>), grid, dim3(256), 0, s, p);
+        }
+        hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads, batch), dim3(256), 0, s, p);
+        dim3 grid(round_up((plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits * batch, kNumXcd));
+        if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 1>), grid, dim3(256), 0, s, p);
+        else                 hipLaunchKernelGGL((score_sweep_kernel<64, 1>), grid, dim3(256), 0, s, p);
+    } else {
+        p.b_splits = 0;          // no language queries in the whole batch: the mean is empty, only beta applies
+    }
+    hipLaunchKernelGGL(score_final_kernel, dim3((n_video + 255) / 256, batch), dim3(256), 0, s, p);
+    return launch_status();
 }

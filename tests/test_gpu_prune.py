@@ -142,9 +142,9 @@ def test_score_planted_keys_on_top_and_chain_to_select(B):
 
 
 def test_score_ragged_batch_equals_per_request_oracle(B):
-    """Three requests of different video and prompt lengths in one call (host prefix offsets): every
-    request's scores equal the oracle's for that request alone, for both normalisation domains,
-    with and without accumulation into existing scores."""
+    """Three requests of different video and prompt lengths in one call (device prefix offsets, one set
+    of launches): every request's scores equal the oracle's for that request alone, for both
+    normalisation domains, with and without accumulation into existing scores."""
     hq, hkv, d = 8, 2, 128
     Vs, Ls = [700, 196, 1300], [40, 70, 9]
     qs = [rnd_bits((L, hq, d), 300 + i) for i, L in enumerate(Ls)]
@@ -159,11 +159,46 @@ def test_score_ragged_batch_equals_per_request_oracle(B):
         again = B.score(qd, kd, 0, 0, -1, scale, norm_mode=mode, beta=1.0, scores=got.clone(),
                         cu_text=cu_text, cu_keys=cu_keys, cu_video=cu_video)
         torch.cuda.synchronize()
+        # the same call with offsets that already live on the device (the host passes only the maxima)
+        dev_off = B.score(qd, kd, 0, 0, -1, scale, norm_mode=mode, cu_text=i32(cu_text), cu_keys=i32(cu_keys),
+                          cu_video=i32(cu_video), max_n_text=max(Ls), max_n_keys=max(V + L for V, L in zip(Vs, Ls)),
+                          max_n_video=max(Vs), total_video=sum(Vs))
+        torch.cuda.synchronize()
+        assert torch.equal(dev_off, got)
         for i, (V, L) in enumerate(zip(Vs, Ls)):
             want = oracle.score(qs[i], ks[i], 0, V, V, scale, norm_mode=mode)
             sl = slice(int(cu_video[i]), int(cu_video[i + 1]))
             assert_scores_close(got[sl], want, f"request {i} mode{mode}")
             assert_scores_close(again[sl], 2 * want, f"request {i} mode{mode} accumulated")
+
+
+def test_score_ragged_batch_with_row_lse_prefix_and_empty_requests(B):
+    """A batch with a prefix before the video, a request without text queries, one without video tokens,
+    caller-supplied row normalisers and 7B-shaped heads, all in one set of launches."""
+    hq, hkv, d, P = 28, 4, 128, 3
+    Vs, Ls = [400, 0, 196, 650], [30, 12, 0, 70]
+    qs = [rnd_bits((L, hq, d), 330 + i) for i, L in enumerate(Ls)]
+    ks = [rnd_bits((P + V + L, hkv, d), 340 + i) for i, (V, L) in enumerate(zip(Vs, Ls))]
+    cu_text = np.concatenate([[0], np.cumsum(Ls)])
+    cu_keys = np.concatenate([[0], np.cumsum([P + V + L for V, L in zip(Vs, Ls)])])
+    cu_video = np.concatenate([[0], np.cumsum(Vs)])
+    qd, kd = dev_bf16(np.concatenate(qs)), dev_bf16(np.concatenate(ks))
+    scale = 1.0 / np.sqrt(d)
+    wants, lses = [], []
+    for i, (V, L) in enumerate(zip(Vs, Ls)):
+        w_, l_ = oracle.score(qs[i], ks[i], P, V, P + V, scale, want_lse=True)
+        wants.append(w_); lses.append(l_)
+    base = torch.full((int(cu_video[-1]),), 0.25, device="cuda")
+    got = B.score(qd, kd, P, 0, -1, scale, cu_text=cu_text, cu_keys=cu_keys, cu_video=cu_video,
+                  beta=1.0, scores=base.clone())
+    lse = torch.tensor(np.concatenate(lses), dtype=torch.float32).cuda()
+    got2 = B.score(qd, kd, P, 0, -1, scale, cu_text=cu_text, cu_keys=cu_keys, cu_video=cu_video, row_lse=lse)
+    torch.cuda.synchronize()
+    for i, V in enumerate(Vs):
+        sl = slice(int(cu_video[i]), int(cu_video[i + 1]))
+        if V:
+            assert_scores_close(got[sl], 0.25 + wants[i], f"request {i} accumulated")
+            assert_scores_close(got2[sl], wants[i], f"request {i} row_lse")
 
 
 def test_score_full_size_72b_layer_two_head_groups(B):
@@ -226,11 +261,15 @@ def test_score_argument_errors(B):
     assert e.value.status == -1
     with pytest.raises(B.SpecVLMError):
         B.score(q, k, 0, 16, 16, 0.1, norm_mode=3)
+    # a request whose video span exceeds its keys (sizes live on the device): skipped, its scores untouched
     q8 = torch.zeros((8, 4, 64), dtype=torch.bfloat16, device="cuda")
     k40 = torch.zeros((40, 1, 64), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.SpecVLMError) as e:          # the second request's video span exceeds its keys
-        B.score(q8, k40, 0, 0, -1, 0.1, cu_text=[0, 4, 8], cu_keys=[0, 30, 40], cu_video=[0, 10, 26])
-    assert e.value.status == -1
+    s = torch.full((26,), -5.0, device="cuda")
+    B.score(q8, k40, 0, 0, -1, 0.1, cu_text=[0, 4, 8], cu_keys=[0, 30, 40], cu_video=[0, 10, 26], scores=s)
+    torch.cuda.synchronize()
+    got = s.cpu().numpy()
+    np.testing.assert_allclose(got[:10], np.full(10, np.mean([1.0 / (27 + i) for i in range(4)])), rtol=1e-5)
+    assert (got[10:] == -5.0).all()
 
 
 # ----------------------------------------------------------------- select
