@@ -356,6 +356,23 @@ def main():
             other[f"verify_attn {name} {layout}"] = {
                 "us_per_layer": r["verify_attn_us_per_layer"], "gbs": r["value"],
                 "pct_of_hbm_peak": round(100.0 * r["value"] / HBM_PEAK_GBS, 1), "shape": r["config"]["workload"]}
+        # tree verification at the 72B shape: a seeded 26-node static tree (208 query rows per kv head, four
+        # row groups) whose nodes are the last 26 rows of the same caches
+        n_nodes = 26
+        tmask = torch.from_numpy(synth.ancestor_masks(synth.make_tree(n_nodes, seed=synth.SEED_BASE + 26))
+                                 .view(np.int64)).to(dev)
+        q_tree = randn_bf16((L, n_nodes, hq, d))
+        out_t = torch.empty((n_nodes, hq, d), dtype=torch.bfloat16, device=dev)
+        ws_t = B.new_workspace(B.decode_attn_workspace_bytes(1, n_nodes, kv_len, hq, hkv, d, 0), dev)
+        us_t = timed_replays(torch, graph_of(torch, lambda: [B.tree_attn(q_tree[l], k_all[l], v_all[l], scale, tmask,
+                                                                         out=out_t, workspace=ws_t)
+                                                             for l in range(L)], args.eager), 5) / L
+        tree_bytes = 2 * kv_len * hkv * d * 2 + 2 * n_nodes * hq * d * 2
+        other["tree verify 26 nodes, 72b-full caches"] = {
+            "us_per_layer": round(us_t, 2), "gbs": round(tree_bytes / (us_t * 1e-6) / 1e9, 1),
+            "pct_of_hbm_peak": round(100.0 * tree_bytes / (us_t * 1e-6) / 1e9 / HBM_PEAK_GBS, 1),
+            "note": "algorithmic bytes count K and V once; the four row groups of a head re-read them (L2)"}
+        del q_tree
         # rejection-sampling accept at the long-video configuration's size (gamma 7, vocab 152 064)
         w3 = synth.scaled(synth.WORKLOADS["32b-long"], gamma=7)
         a3 = synth.make_accept_inputs(1, w3.gamma, w3.vocab, synth.SEED_BASE + 3077, greedy=False)

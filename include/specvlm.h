@@ -232,7 +232,10 @@ int specvlm_gather_kv(
  *               lengths finish together.
  *   Workspace: the query takes the same batch, maxima, head counts and
  *               num_splits as the call (it is pure: it depends on nothing else).
- * Limits: (H_q/H_kv) * q_len <= 64.
+ * Limits: q_len <= 64.  Up to 64 query rows per kv head ((H_q/H_kv) * q_len)
+ *   read K and V from memory exactly once; beyond that the rows are processed in
+ *   groups of at most 64 (one workgroup per group, head and key range) and each
+ *   group reads the key range again, its neighbours' copy mostly still cached.
  * -------------------------------------------------------------------------- */
 size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int kv_len,
                                            int n_q_heads, int n_kv_heads, int head_dim,

@@ -66,7 +66,8 @@ struct AttnParams {
     int num_splits, split_keys;
     float* part_o;           // [batch*H_kv][num_splits][rows_pad][D] unnormalised partial outputs
     float* part_ml;          // [batch*H_kv][num_splits][rows_pad][2] (running max in log2 units, sum)
-    int rows_pad;
+    int rows_pad;            // rows per partial slot: n_rgroups * (row blocks per workgroup) * 16
+    int n_rgroups;           // groups of at most 4 row blocks that share a (head, split): one workgroup each
     int n_work;
     const uint64_t* block_mask;  // [sum q_len] tree masks of the block's queries, or null (chain)
     int balanced;            // batch mode: balanced pieces (see attn_balance) instead of uniform splits
@@ -104,6 +105,7 @@ __device__ __forceinline__ AttnBalance attn_balance(const AttnParams& p, int til
     return r;
 }
 constexpr int kMaxSplits = 256;
+constexpr int kMaxQueryBlock = 64;      // queries per request: a row's view of its block is one 64-bit mask
 constexpr int kMaxDevices = 64;         // per-device host state (kernel attributes, scratch addresses)
 constexpr int kTargetWorkgroups = 192;  // workgroups of a single-request launch
 
@@ -191,8 +193,8 @@ void attn_split_kernel(const AttnParams p)
 
     // One piece of work: keys [k_begin, k_end) of (request b, kv head g) for all its query rows;
     // the result goes to partial slot slot0 (in units of rows), or straight to the output.
-    auto piece = [&](const int b, const int g, const int k_begin, const int k_end, const int64_t slot0,
-                     const bool direct) {
+    auto piece = [&](const int b, const int g, const int row0, const int k_begin, const int k_end,
+                     const int64_t slot0, const bool direct) {
     int q0 = 0, ql = p.q_len, kv0 = 0, kvl = p.kv_len;
     if (p.cu_q) { q0 = p.cu_q[b]; ql = p.cu_q[b + 1] - q0; }
     if (p.cu_kv) { kv0 = p.cu_kv[b]; kvl = p.cu_kv[b + 1] - kv0; }
@@ -207,7 +209,7 @@ void attn_split_kernel(const AttnParams p)
     unsigned char* q_stage = smem + (NS - 1) * (2 * TILE_BYTES) + wave * (KK * 1024);
     static_assert(MB * KS * KK * 1024 <= 2 * TILE_BYTES, "Q staging must fit in one ring stage");
     {
-        const int row = mb * 16 + r;
+        const int row = row0 + mb * 16 + r;
         const bool live = row < n_rows;             // padding rows read row 0: finite, never stored
         const int t = live ? row / p.group : 0;
         const int h = g * p.group + (live ? row % p.group : 0);
@@ -369,7 +371,7 @@ void attn_split_kernel(const AttnParams p)
 
     // ---- epilogue ----
     l_run = quad_sum(l_run);
-    const int row = mb * 16 + r;
+    const int row = row0 + mb * 16 + r;
     const int t_row = row / p.group, h_row = g * p.group + row % p.group;
     const int64_t slot = slot0 + row;
     if constexpr (KS == 1) {
@@ -460,7 +462,7 @@ void attn_split_kernel(const AttnParams p)
     };   // piece
 
     if (!p.balanced) {
-        // Uniform splits.  Dispatch order: the kv heads of one (request, split) are neighbours.
+        // Uniform splits.  Dispatch order: the kv heads of one (request, row group, split) are neighbours.
         // Workgroups are dealt to the XCDs round-robin by id, so with 8 kv heads every split of head
         // g runs on XCD g: its partial results stay near that XCD, where the merge kernel (same
         // head-to-XCD order) finds them.  Token-major caches interleave the heads inside every token
@@ -468,7 +470,10 @@ void attn_split_kernel(const AttnParams p)
         const int vid = blockIdx.x;
         const int g = vid % p.n_kv_heads, rest = vid / p.n_kv_heads;
         const int split = rest % p.num_splits;
-        const int b = rest / p.num_splits;
+        // more than 64 query rows per kv head: groups of MB row blocks, one workgroup each; the groups of
+        // a (head, split) re-read its keys, as neighbours in time on one XCD (mostly from its L2)
+        const int rg = (rest / p.num_splits) % p.n_rgroups;
+        const int b = rest / (p.num_splits * p.n_rgroups);
         int ql = p.q_len, kvl = p.kv_len;
         if (p.cu_q) ql = p.cu_q[b + 1] - p.cu_q[b];
         if (p.cu_kv) kvl = p.cu_kv[b + 1] - p.cu_kv[b];
@@ -476,7 +481,7 @@ void attn_split_kernel(const AttnParams p)
         const int k_begin = split * p.split_keys;
         if (k_begin >= kvl) return;                     // the merge reads only the live splits
         const int bh = b * p.n_kv_heads + g;
-        piece(b, g, k_begin, min(kvl, k_begin + p.split_keys),
+        piece(b, g, rg * (MB * 16), k_begin, min(kvl, k_begin + p.split_keys),
               ((int64_t)bh * p.num_splits + split) * p.rows_pad, p.num_splits == 1);
         return;
     }
@@ -524,7 +529,7 @@ void attn_split_kernel(const AttnParams p)
         const int t = (int)(x - base);
         const int n = (int)min((int64_t)(tiles - t), x_end - x);
         const int kvl = p.cu_kv[b + 1] - p.cu_kv[b];
-        piece(b, g, t * TK, min(kvl, (t + n) * TK), (int64_t)((j + b) * H + g) * p.rows_pad, false);
+        piece(b, g, 0, t * TK, min(kvl, (t + n) * TK), (int64_t)((j + b) * H + g) * p.rows_pad, false);
         x += n;
         __syncthreads();                                // the next piece reuses the ring and the exchange buffer
     }
@@ -676,17 +681,26 @@ void attn_merge_rows_kernel(const AttnParams p)
 // ---------------------------------------------------------------- host side ----
 // A batch whose split count is left to the library is cut into balanced pieces by the kernels
 // themselves (they know the request lengths; the host only knows their maximum).
-static bool attn_is_balanced(int batch, int num_splits, int n_kv_heads)
+static bool attn_is_balanced(int batch, int num_splits, int n_kv_heads, int rows)
 {
-    return batch > 1 && batch <= kMaxBalancedBatch && num_splits == 0 && n_kv_heads <= kNumCu;
+    return batch > 1 && batch <= kMaxBalancedBatch && num_splits == 0 && n_kv_heads <= kNumCu && rows <= 64;
 }
 
-static int choose_splits(int batch, int kv_len, int n_kv_heads, int num_splits)
+// Query rows of a kv head beyond 64 (long chains, draft trees) are cut into groups of equal size,
+// at most 4 row blocks of 16 each: n groups, mb row blocks per group.
+static void attn_row_groups(int rows, int* n_groups, int* mb)
+{
+    const int blocks = (rows + 15) / 16;
+    *n_groups = (blocks + 3) / 4;
+    *mb = (blocks + *n_groups - 1) / *n_groups;
+}
+
+static int choose_splits(int batch, int kv_len, int n_kv_heads, int n_rgroups, int num_splits)
 {
     const int max_by_len = (kv_len + 127) / 128;              // at least two tiles per split
     int s = num_splits;
     if (s <= 0) {
-        const int heads = batch * n_kv_heads;
+        const int heads = batch * n_kv_heads * n_rgroups;
         // One request: a single round of workgroups, about three per four CUs.  Every workgroup then
         // streams the same share from start to end and HBM is saturated well before all CUs are
         // busy; more, smaller splits only add partial results and rounds (measured on 8 kv heads:
@@ -777,15 +791,17 @@ extern "C" size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int 
         n_q_heads % n_kv_heads || (head_dim != 64 && head_dim != 128))
         return 0;
     const int rows = (n_q_heads / n_kv_heads) * q_len;
-    if (rows > 64) return 0;
-    const int rows_pad = round_up(rows, 16);
+    if (q_len > kMaxQueryBlock) return 0;
+    int n_rgroups, mb;
+    attn_row_groups(rows, &n_rgroups, &mb);
+    const int rows_pad = n_rgroups * mb * 16;
     size_t slots;
-    if (attn_is_balanced(batch, num_splits, n_kv_heads)) {
+    if (attn_is_balanced(batch, num_splits, n_kv_heads, rows)) {
         slots = (size_t)(kNumCu + batch * n_kv_heads) * rows_pad;
         return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) +
                align256((size_t)batch * n_kv_heads * 2 * sizeof(int32_t));
     } else {
-        const int splits = choose_splits(batch, kv_len, n_kv_heads, num_splits);
+        const int splits = choose_splits(batch, kv_len, n_kv_heads, n_rgroups, num_splits);
         if (splits == 1) return 256;
         slots = (size_t)batch * n_kv_heads * splits * rows_pad;
     }
@@ -814,11 +830,12 @@ static int attn_impl(
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return SPECVLM_EUNSUPPORTED;
     const int group = n_q_heads / n_kv_heads;
     const int rows = group * q_len;
-    if (rows > 64) return SPECVLM_EUNSUPPORTED;
+    if (q_len > kMaxQueryBlock) return SPECVLM_EUNSUPPORTED;
     // per-lane key offsets are 32-bit byte offsets from the request's first row
     if (kv_tok_stride <= 0 || (int64_t)kv_len * kv_tok_stride * 2 >= ((int64_t)1 << 32))
         return SPECVLM_EUNSUPPORTED;
-    const int mb = (rows + 15) / 16;
+    int n_rgroups, mb;
+    attn_row_groups(rows, &n_rgroups, &mb);
 
     AttnParams p;
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
@@ -829,13 +846,14 @@ static int attn_impl(
     p.batch = batch; p.q_len = q_len; p.kv_len = kv_len;
     p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads; p.group = group;
     p.scale_log2 = softmax_scale * kLog2e;
-    p.balanced = attn_is_balanced(batch, num_splits, n_kv_heads) ? 1 : 0;
+    p.balanced = attn_is_balanced(batch, num_splits, n_kv_heads, rows) ? 1 : 0;
     p.max_wg = kNumCu;
     p.tile_keys = mb == 1 ? 128 : 64;                 // TK of the launch shape chosen below
-    p.num_splits = p.balanced ? 2 : choose_splits(batch, kv_len, n_kv_heads, num_splits);
+    p.num_splits = p.balanced ? 2 : choose_splits(batch, kv_len, n_kv_heads, n_rgroups, num_splits);
     p.split_keys = (kv_len + p.num_splits - 1) / p.num_splits;
-    p.rows_pad = mb * 16;
-    p.n_work = p.balanced ? p.max_wg : batch * n_kv_heads * p.num_splits;
+    p.rows_pad = n_rgroups * mb * 16;
+    p.n_rgroups = n_rgroups;
+    p.n_work = p.balanced ? p.max_wg : batch * n_kv_heads * p.num_splits * n_rgroups;
     p.part_o = nullptr; p.part_ml = nullptr; p.seg_table = nullptr;
     if (p.num_splits > 1) {
         const size_t need = specvlm_decode_attn_workspace_bytes(batch, q_len, kv_len, n_q_heads,

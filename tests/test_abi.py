@@ -39,7 +39,8 @@ def test_status_strings_and_version(B):
 def test_workspace_queries_are_pure_host_functions(B):
     assert B.decode_attn_workspace_bytes(1, 6, 12806, 64, 8, 128) > 0
     assert B.decode_attn_workspace_bytes(1, 6, 12806, 64, 8, 96) == 0       # unsupported head_dim
-    assert B.decode_attn_workspace_bytes(1, 9, 12806, 64, 8, 128) == 0      # 72 rows per kv head
+    assert B.decode_attn_workspace_bytes(1, 9, 12806, 64, 8, 128) > 0       # 72 rows per kv head: two row groups
+    assert B.decode_attn_workspace_bytes(1, 65, 12806, 64, 8, 128) == 0     # more than 64 queries per request
     assert B.score_workspace_bytes(256, 12800, 12544, 64, 8, 128) > 0
     assert B.accept_workspace_bytes(1, 5, 152064, True) >= B.accept_workspace_bytes(1, 5, 152064, False) > 0
     assert B.lib().specvlm_select_workspace_bytes(8, 32768) == 0

@@ -59,6 +59,12 @@ def run_case(B, q_len, kv_len, hq, hkv, d, seed, num_splits=0, scale=None, head_
     (2, 9000, 4, 1, 64, 70),       # the same for d 64 (prefetch covers 64)
     (6, 200, 8, 1, 128, 1),        # one split of three tiles and a bit: the ring wraps once
     (6, 70, 16, 2, 128, 0),        # a split shorter than the ring: its last tile is loaded twice
+    (9, 900, 8, 1, 64, 0),         # 72 rows per kv head: two groups of three row blocks
+    (16, 3000, 16, 2, 128, 0),     # chain of gamma 15 at group 8: 128 rows, two groups of four row blocks
+    (16, 3000, 16, 2, 128, 1),
+    (16, 700, 28, 4, 128, 3),      # group 7: 112 rows
+    (64, 300, 16, 1, 64, 2),       # the longest block: 64 queries x group 16 = 1024 rows, sixteen groups
+    (13, 13, 8, 1, 128, 0),        # more than 64 rows and nothing but the block itself
 ])
 def test_matches_oracle(B, q_len, kv_len, hq, hkv, d, splits):
     run_case(B, q_len, kv_len, hq, hkv, d, seed=100 + q_len + kv_len, num_splits=splits)
@@ -161,8 +167,8 @@ def test_argument_errors(B):
     with pytest.raises(B.SpecVLMError) as e:
         B.decode_attn(q96, k96, k96, 0.1)
     assert e.value.status == -2
-    qbig = torch.zeros((9, 8, 64), dtype=torch.bfloat16, device="cuda")   # 72 rows per kv head
-    kbig = torch.zeros((64, 1, 64), dtype=torch.bfloat16, device="cuda")
+    qbig = torch.zeros((65, 8, 64), dtype=torch.bfloat16, device="cuda")  # more than 64 queries per request
+    kbig = torch.zeros((128, 1, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(B.SpecVLMError) as e:
         B.decode_attn(qbig, kbig, kbig, 0.1)
     assert e.value.status == -2

@@ -33,6 +33,11 @@ def dev_mask(m):
     (5, 40, 8, 2, 64, 1, 3),          # the block is a third of the cache
     (12, 500, 10, 2, 128, 3, 4),      # group 5, 60 rows
     (26, 2000, 2, 1, 128, 0, 5),      # a 26-node tree (EAGLE-sized), 2 q heads
+    (26, 6400, 64, 8, 128, 0, 6),     # the same tree size at the 72B head shape: 208 rows per kv head
+    (60, 3000, 64, 8, 128, 0, 7),     # 60 nodes at 64/8 heads: 480 rows per kv head, eight row groups
+    (60, 2100, 28, 4, 128, 0, 8),     # 60 nodes at the 7B head shape (group 7): 420 rows
+    (26, 2100, 28, 4, 128, 4, 9),
+    (64, 500, 40, 8, 128, 0, 10),     # the largest tree the mask holds, 32B head shape (group 5)
 ])
 def test_tree_attn_matches_oracle(B, n_nodes, kv_ctx, hq, hkv, d, splits, seed):
     parent = synth.make_tree(n_nodes, seed=40 + seed)
@@ -56,6 +61,29 @@ def test_chain_mask_equals_decode_attn_bitwise(B):
     b = B.tree_attn(qd, kd, vd, 0.088, dev_mask(chain), num_splits=5)
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_tree_attn_ragged_batch_of_large_trees(B):
+    """Trees of 26-60 nodes at 64/8 heads in one launch with cu arrays (more than 64 rows per kv head:
+    uniform key splits, several row groups per head)."""
+    hq, hkv, d = 64, 8, 128
+    trees = [synth.make_tree(n, seed=190 + i) for i, n in enumerate((26, 60, 9))]
+    lens = [900 + 26, 64 + 60, 2300 + 9]
+    qs = [rnd_bits((t.size, hq, d), 200 + i) for i, t in enumerate(trees)]
+    ks = [rnd_bits((n, hkv, d), 210 + i) for i, n in enumerate(lens)]
+    vs = [rnd_bits((n, hkv, d), 220 + i) for i, n in enumerate(lens)]
+    masks = [synth.ancestor_masks(t) for t in trees]
+    cu_q = torch.tensor(np.concatenate([[0], np.cumsum([t.size for t in trees])]), dtype=torch.int32).cuda()
+    cu_kv = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32).cuda()
+    out = B.tree_attn(dev_bf16(np.concatenate(qs)), dev_bf16(np.concatenate(ks)), dev_bf16(np.concatenate(vs)),
+                      0.088, dev_mask(np.concatenate(masks)), cu_q=cu_q, cu_kv=cu_kv,
+                      max_q_len=60, max_kv_len=max(lens))
+    torch.cuda.synchronize()
+    o = 0
+    for i, t in enumerate(trees):
+        want, _ = oracle.tree_attn(qs[i], ks[i], vs[i], masks[i], 0.088)
+        assert_attn_close(out[o:o + t.size], want, f"large tree, request {i}")
+        o += t.size
 
 
 def test_tree_attn_ragged_batch(B):
