@@ -64,7 +64,7 @@ template <int E>
 __global__ __launch_bounds__(kSelThreads)
 void select_kernel(const SelectParams p)
 {
-    __shared__ int s_hist[kSelWaves][256];
+    __shared__ int s_hist[2][kSelWaves][257];    // per-wave histograms (padded: see below); the passes alternate between two sets
     __shared__ int s_tot[256];
     __shared__ int s_wave2[2][kSelWaves];
     __shared__ int s_pick[2];
@@ -84,6 +84,8 @@ void select_kernel(const SelectParams p)
         const int idx = first + e;
         raw[e] = (e < per && idx < n) ? sc[idx] : 0.f;
     }
+    // the first pass's histograms are cleared while the scores are on their way
+    for (int i = tid; i < kSelWaves * 257; i += kSelThreads) (&s_hist[0][0][0])[i] = 0;
     const int k = p.k_top[b], budget = p.keep_budget[b];
     const int out0 = p.cu_keep ? p.cu_keep[b] : 0;
     const bool bad = n < 0 || n > E * kSelThreads || n > p.max_n_video || k < 0 || k > budget || budget > n;
@@ -106,8 +108,7 @@ void select_kernel(const SelectParams p)
     if (k > 0) {
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = 24 - 8 * pass;
-            for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&s_hist[0][0])[i] = 0;
-            __syncthreads();
+            if (pass == 0) __syncthreads();             // the cleared histograms are visible
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const bool match = ((valid >> e) & 1) && ((key[e] & known) == prefix);
@@ -118,20 +119,24 @@ void select_kernel(const SelectParams p)
                 const int d0 = __builtin_amdgcn_readlane(digit, leader);      // leader is wave-uniform: no LDS crossbar trip
                 const uint64_t same = __ballot(match && digit == d0);
                 if (same == act) {                      // whole wave agrees: one add
-                    if (lane == leader) atomicAdd(&s_hist[wave][d0], __popcll(act));
+                    if (lane == leader) atomicAdd(&s_hist[pass & 1][wave][d0], __popcll(act));
                 } else if (match) {
                     // The 16 per-wave histograms are summed afterwards, so a lane may add to any of
                     // them: lanes of one instruction that share a digit are spread over all 16 copies
                     // (an LDS atomic serialises over the lanes that hit one address, and the leading
                     // digit of attention scores, sign and exponent, takes only a handful of values).
-                    atomicAdd(&s_hist[(wave + lane) & (kSelWaves - 1)][digit], 1);
+                    // A copy is 257 words long, so the 16 copies of a digit lie in 16 different banks.
+                    atomicAdd(&s_hist[pass & 1][(wave + lane) & (kSelWaves - 1)][digit], 1);
                 }
             }
+            // the other set (read for the last time two barriers ago) is cleared for the next pass
+            if (pass < 3)
+                for (int i = tid; i < kSelWaves * 257; i += kSelThreads) (&s_hist[(pass + 1) & 1][0][0])[i] = 0;
             __syncthreads();
             if (tid < 256) {
                 int t = 0;
 #pragma unroll
-                for (int w = 0; w < kSelWaves; ++w) t += s_hist[w][tid];
+                for (int w = 0; w < kSelWaves; ++w) t += s_hist[pass & 1][w][tid];
                 s_tot[tid] = t;
             }
             __syncthreads();
@@ -195,16 +200,19 @@ void select_kernel(const SelectParams p)
     // ---- Stage II: uniform stride over the remainder ----
     const uint64_t rem_mask = valid & ~top;
     const int rho_before = (first < n ? first : n) - top_before;
-    const uint64_t R = (uint64_t)(n - k), U = (uint64_t)(budget - k);
+    // n <= 65536, so every product below (rank x U, index x R, each factor <= 65536 and one of them
+    // < 65536) fits 32 bits: unsigned 32-bit divisions, exact
+    const uint32_t R = (uint32_t)(n - k), U = (uint32_t)(budget - k);
     uint64_t uni = 0;
     int uni_before = 0;                                           // stride picks with a rank below mine
     if (U > 0) {
-        uint64_t t = ((uint64_t)rho_before * U + R - 1) / R;      // first stride index at or after my ranks
+        uint32_t t = (uint32_t)(((uint64_t)rho_before * U + R - 1) / R);   // first stride index at or after my ranks
         uni_before = (int)(t < U ? t : U);
         if (t < U && rem_mask) {
-            uint64_t q = (t * R) / U, frac = (t * R) % U;         // rank floor(t*R/U)
-            const uint64_t step_q = R / U, step_f = R % U;
-            uint64_t rho = (uint64_t)rho_before;
+            const uint32_t tr = t * R;                            // t <= U - 1: the product fits
+            uint32_t q = tr / U, frac = tr % U;                   // rank floor(t*R/U)
+            const uint32_t step_q = R / U, step_f = R % U;
+            uint32_t rho = (uint32_t)rho_before;
             for (uint64_t m = rem_mask; m && t < U; ++rho) {
                 const uint64_t bit = m & (~m + 1);
                 m ^= bit;
