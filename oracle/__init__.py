@@ -20,11 +20,20 @@ _LIB = os.path.join(_HERE, "libspecvlm_oracle.so")
 _lib = None
 
 
+# SPECVLM_ORACLE_SANITIZE=1: an AddressSanitizer + UndefinedBehaviorSanitizer build of the same source
+# (tests/test_oracle_sanitized.py runs the oracle's pins under it in a child process that preloads
+# the sanitizer runtime).
+_SANITIZE = os.environ.get("SPECVLM_ORACLE_SANITIZE") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libspecvlm_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (fp64 loops, OpenMP over rows only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall",
-                               "-o", _LIB, _SRC, "-lm"])
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
