@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libspecvlm.so")
+# SPECVLM_LIB names another build of the same library (the host-sanitized one the CPU tests make)
+LIB_PATH = os.environ.get("SPECVLM_LIB") or os.path.join(_HERE, "libspecvlm.so")
 _lib = None
 
 EXPORTS = (

@@ -26,10 +26,19 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
+# A second build for the CPU tests: the HOST code of the same sources (argument validation, launch
+# planning, workspace sizing) under AddressSanitizer + UndefinedBehaviorSanitizer; device code unchanged.
+LIB_HOSTSAN = os.path.join(HERE, "libspecvlm_hostsan.so")
+HOSTSAN_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-shared-libsan"]
+
+
+def build(verbose: bool = False, host_sanitizers: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"),
-           "-I", os.path.join(HERE, "csrc"), "-o", LIB, *sources()]
+    out_lib = LIB_HOSTSAN if host_sanitizers else LIB
+    flags = [f if f != "-O3" else "-O1" for f in HIPCC_FLAGS] + HOSTSAN_FLAGS if host_sanitizers else HIPCC_FLAGS
+    cmd = [hipcc, *flags, "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(HERE, "csrc"), "-o", out_lib, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -40,7 +49,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and out.strip():
         print(out)
-    return LIB
+    return out_lib
 
 
 if __name__ == "__main__":
