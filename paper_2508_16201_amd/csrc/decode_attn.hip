@@ -64,7 +64,7 @@ struct AttnParams {
     int batch, q_len, kv_len, n_q_heads, n_kv_heads, group;
     float scale_log2;        // softmax_scale * log2(e)
     int num_splits, split_keys;
-    float* part_o;           // [batch*H_kv][num_splits][rows_pad][D] unnormalised partial outputs
+    __bf16* part_o;          // [batch*H_kv][num_splits][rows_pad][D] unnormalised partial outputs (bf16: see the merge kernel)
     float* part_ml;          // [batch*H_kv][num_splits][rows_pad][2] (running max in log2 units, sum)
     int rows_pad;            // rows per partial slot: n_rgroups * (row blocks per workgroup) * 16
     int n_rgroups;           // groups of at most 4 row blocks that share a (head, split): one workgroup each
@@ -391,13 +391,13 @@ void attn_split_kernel(const AttnParams p)
             if (p.lse && c == 0)
                 p.lse[(int64_t)(q0 + t_row) * p.n_q_heads + h_row] = (m_run + fast_log2(l_run)) * kLn2;
         } else {
-            float* po = p.part_o + slot * D;
+            __bf16* po = p.part_o + slot * D;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < DJ / 4; ++jj) {
                     floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
-                    *reinterpret_cast<floatx4*>(po + (4 * c + i) * DJ + 4 * jj) = x;
+                    *reinterpret_cast<bf16x4*>(po + (4 * c + i) * DJ + 4 * jj) = __builtin_convertvector(x, bf16x4);
                 }
             if (c == 0) { p.part_ml[slot * 2] = m_run; p.part_ml[slot * 2 + 1] = l_run; }
         }
@@ -453,9 +453,9 @@ void attn_split_kernel(const AttnParams p)
             if (p.lse && c == 0 && ks == 0)
                 p.lse[(int64_t)(q0 + t_row) * p.n_q_heads + h_row] = (m_all + fast_log2(l_all)) * kLn2;
         } else {
-            float* po = p.part_o + slot * D + col0;
+            __bf16* po = p.part_o + slot * D + col0;
 #pragma unroll
-            for (int qd = 0; qd < CPL / 4; ++qd) *reinterpret_cast<floatx4*>(po + 4 * qd) = acc[qd];
+            for (int qd = 0; qd < CPL / 4; ++qd) *reinterpret_cast<bf16x4*>(po + 4 * qd) = __builtin_convertvector(acc[qd], bf16x4);
             if (c == 0 && ks == 0) { p.part_ml[slot * 2] = m_all; p.part_ml[slot * 2 + 1] = l_all; }
         }
     }
@@ -536,6 +536,10 @@ void attn_split_kernel(const AttnParams p)
 }
 
 // Merge of the split partials: o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s.
+// The partial outputs travel as bf16 (the running maxima and sums stay fp32): each is rounded once, by
+// at most 2^-9 of its own size, and the merged row is a convex combination of them, so the detour adds
+// at most one more rounding of the size the bf16 output carries anyway, and it halves the bytes that
+// the two kernels exchange.
 // One workgroup per (kv head, query row); thread (grp, col) folds the splits grp, grp + GROUPS, ...
 // for 4 output columns.  Every load of the first PRE splits per thread is issued up front, so the
 // kernel costs one memory round trip; each group folds its splits against its own maximum and a
@@ -572,7 +576,7 @@ void attn_merge_kernel(const AttnParams p)
             const int64_t slot = slot0 + (int64_t)s * p.rows_pad;
             const float* ml = p.part_ml + slot * 2;          // the same address across the group: one transaction
             m_i[i] = ml[0]; l_i[i] = ml[1];
-            ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+            ov[i] = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(p.part_o + slot * D + col), floatx4);
         }
     }
     float m_loc = m_i[0];
@@ -590,7 +594,7 @@ void attn_merge_kernel(const AttnParams p)
     for (int s = grp + GROUPS * PRE; s < live; s += GROUPS) {   // more splits than the prefetch covers
         const int64_t slot = slot0 + (int64_t)s * p.rows_pad;
         const float m_s = p.part_ml[slot * 2], l_s = p.part_ml[slot * 2 + 1];
-        const floatx4 o_s = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+        const floatx4 o_s = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(p.part_o + slot * D + col), floatx4);
         const float m_new = fmaxf(m_loc, m_s);
         const float r_new = (m_new == -INFINITY) ? 0.f : m_new;
         const float f_old = fast_exp2(m_loc - r_new), f_s = fast_exp2(m_s - r_new);
@@ -653,7 +657,7 @@ void attn_merge_rows_kernel(const AttnParams p)
             if (s0 + i < live) {
                 const int64_t slot = slot0 + (int64_t)(s0 + i) * p.n_kv_heads * p.rows_pad;   // the next group's piece
                 m_i[i] = p.part_ml[slot * 2]; l_i[i] = p.part_ml[slot * 2 + 1];
-                ov[i] = *reinterpret_cast<const floatx4*>(p.part_o + slot * D + col);
+                ov[i] = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(p.part_o + slot * D + col), floatx4);
             }
         }
         float m_new = m;
@@ -798,14 +802,14 @@ extern "C" size_t specvlm_decode_attn_workspace_bytes(int batch, int q_len, int 
     size_t slots;
     if (attn_is_balanced(batch, num_splits, n_kv_heads, rows)) {
         slots = (size_t)(kNumCu + batch * n_kv_heads) * rows_pad;
-        return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) +
+        return align256(slots * head_dim * sizeof(__bf16)) + align256(slots * 2 * sizeof(float)) +
                align256((size_t)batch * n_kv_heads * 2 * sizeof(int32_t));
     } else {
         const int splits = choose_splits(batch, kv_len, n_kv_heads, n_rgroups, num_splits);
         if (splits == 1) return 256;
         slots = (size_t)batch * n_kv_heads * splits * rows_pad;
     }
-    return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float));
+    return align256(slots * head_dim * sizeof(__bf16)) + align256(slots * 2 * sizeof(float));
 }
 
 static int attn_impl(
@@ -861,8 +865,8 @@ static int attn_impl(
         if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) return SPECVLM_EWORKSPACE;
         const size_t slots = p.balanced ? (size_t)(p.max_wg + batch * n_kv_heads) * p.rows_pad
                                         : (size_t)batch * n_kv_heads * p.num_splits * p.rows_pad;
-        p.part_o = (float*)workspace;
-        p.part_ml = (float*)((char*)workspace + align256(slots * head_dim * sizeof(float)));
+        p.part_o = (__bf16*)workspace;
+        p.part_ml = (float*)((char*)workspace + align256(slots * head_dim * sizeof(__bf16)));
         p.seg_table = (int32_t*)((char*)p.part_ml + align256(slots * 2 * sizeof(float)));   // (used in balanced mode)
     }
     hipStream_t s = (hipStream_t)stream;

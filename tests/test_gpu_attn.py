@@ -81,9 +81,12 @@ def test_splits_agree_within_rounding(B):
     a = B.decode_attn(qd, kd, vd, 0.088, num_splits=1).float()
     b = B.decode_attn(qd, kd, vd, 0.088, num_splits=9).float()
     torch.cuda.synchronize()
-    # one bf16 ulp of the output plus the spread of the bf16-rounded probabilities
-    # (each split layout rounds them against its own running maximum)
-    tol = torch.maximum(a.abs(), b.abs()) * 2.0 ** -7 + 2e-4
+    # Two kernel results, no oracle here: one bf16 ulp of the output (2^-7 relative covers a step
+    # across a binade), plus an absolute term for what does not scale with the output: the
+    # probabilities are rounded to bf16 against each split's own running maximum, and the partial
+    # outputs of the splits travel as bf16 (2^-9 of a partial that may be larger than the merged value
+    # when values of both signs cancel).  Against the fp64 oracle either result is within 4e-4 here.
+    tol = torch.maximum(a.abs(), b.abs()) * 2.0 ** -7 + 6e-4
     assert bool(((a - b).abs() <= tol).all())
 
 
