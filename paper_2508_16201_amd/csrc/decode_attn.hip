@@ -38,11 +38,13 @@
 //     softmax statistics of a row live in lanes r, r+16, r+32, r+48.
 //   O^T = V^T P^T : B = P^T is what the lane already holds (row r, keys
 //     {4c..4c+3} of both 16-key halves); A = V^T needs per lane 8 keys x 1 value
-//     column.  A lane reads 8 (d=128) contiguous value columns of its 8 keys
-//     and an in-lane 16-bit transpose (v_perm) forms the operands.  The
-//     contraction order over keys and the column order of O are permutations
-//     fixed by this layout.  O^T keeps row r in lane column r too, so the
-//     running-max rescale is a per-lane multiply.
+//     column, which the transposing LDS read of gfx950 (ds_read_b64_tr_b16)
+//     delivers from row-major V directly: per PV step two reads (one per
+//     16-key half), no in-register transpose.  V rows are chunk-swizzled for
+//     that read pattern like K rows are for theirs.  Step j yields value
+//     columns 16j..16j+15 (lane (r, c): columns 16j+4c..16j+4c+3 of row r).
+//     O^T keeps row r in lane column r too, so the running-max rescale is a
+//     per-lane multiply.
 #include <atomic>
 
 #include "common.h"
@@ -158,9 +160,38 @@ constexpr int largest_divisor_le(int n, int cap)
     return best;
 }
 
-template <int D> struct ValueVec;
-template <> struct ValueVec<128> { typedef u32x4 type; };
-template <> struct ValueVec<64>  { typedef u32x2 type; };
+// XOR applied to the 16-byte chunk index of value row `key` inside a tile.  The transposing read of
+// one PV step touches, per 32 lanes, 8 consecutive keys x 32 contiguous bytes (two chunks 2j, 2j+1):
+// with the pair index XORed by the key (d = 128: key mod 8; d = 64, two rows per 256 bytes: key/2
+// mod 4) those 8 x 32 bytes fall on 64 distinct banks.
+template <int D> __device__ __forceinline__ constexpr int v_swizzle(int key)
+{
+    return (D == 128) ? ((key & 7) << 1) : (((key >> 1) & 3) << 1);
+}
+
+// ds_read_b64_tr_b16: every lane hands in the address of 8 bytes (four 16-bit elements); inside each
+// group of 16 lanes, lanes 4x..4x+3 together hold "row" x (16 elements), and lane o receives element o
+// of rows 0..3.  Issued as assembly, with the wait below: as a builtin the compiler cannot tell the
+// read from one that aliases the direct-to-LDS loads still in flight and drains them (vmcnt 0) first.
+template <int OFFSET>
+__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t lds_addr)
+{
+    u32x2 v;
+    __asm__ volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=&v"(v) : "v"(lds_addr), "n"(OFFSET));
+    return v;
+}
+
+// Waits for this wave's LDS reads; the fragments pass through so that their uses stay behind the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait_fragments(bf16x8 (&f)[N])
+{
+    static_assert(N == 4 || N == 8, "one fragment per 16 value columns");
+    if constexpr (N == 8)
+        __asm__ volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+    else
+        __asm__ volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+}
 
 template <int D, int MB, int KS, int TK, int NS, bool STREAM>
 __global__ __launch_bounds__(MB * KS * kWave)
@@ -181,7 +212,6 @@ void attn_split_kernel(const AttnParams p)
     constexpr int LDS_STRIDE = D + 4;            // merge buffer row stride (floats)
     static_assert(NCHUNK % KS == 0, "chunks must divide among the key-split waves");
     static_assert(NS >= 2 && NS <= 5, "ring depth");
-    typedef typename ValueVec<D>::type vvec_t;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -240,9 +270,11 @@ void attn_split_kernel(const AttnParams p)
             // rows past the split's end are masked in the compute: re-read its last row
             // (a cache hit) instead of pulling the neighbour split's keys from HBM
             const uint32_t key = (uint32_t)min(base + kl, k_end - 1);
-            // K rows are chunk-swizzled so operand reads spread over the banks
-            const int swz = (D == 128) ? (kl & 15) : ((kl >> 1) & 7);
-            const int chunk = is_v ? ld_chunk : (ld_chunk ^ swz);
+            // K and V rows are chunk-swizzled so the operand reads spread over the banks: K for 16 keys x
+            // one chunk per 16 lanes, V for the transposing read (8 keys x two neighbouring chunks per
+            // 32 lanes, see v_swizzle)
+            const int swz = is_v ? v_swizzle<D>(kl) : ((D == 128) ? (kl & 15) : ((kl >> 1) & 7));
+            const int chunk = ld_chunk ^ swz;
             const char* src = (is_v ? vbase : kbase) + (key * tok_bytes + (uint32_t)chunk * 16u);
             unsigned char* dst = st + n * 1024;     // + lane * 16 by the hardware
             // a large cache is read once per launch: non-temporal, so it does not displace what is reused;
@@ -296,12 +328,22 @@ void attn_split_kernel(const AttnParams p)
                     s[i] = (key >= k_end || in_block_hidden) ? -INFINITY : s[i];
                 }
             }
-            // values of the lane's 8 keys: 4c+i (i<4) and 16+4c+(i-4)
-            vvec_t vr[8];
+            // V^T fragments of the lane's 8 keys (4c+i and 16+4c+i, i < 4) by the transposing LDS read:
+            // the 16 lanes of quarter c hand in the rows of keys 4c + x (x = r/4; four lanes per key,
+            // 8 bytes each, together columns 16j..16j+15) and lane r receives column 16j + r of the four
+            // keys -- the A operand of step j with no in-register transpose.
+            bf16x8 vf[DJ];
+            {
+                const int kl = chunk * kChunkKeys + 4 * c + (r >> 2);           // (the second half is 16 rows on)
+                const int pair_swz = v_swizzle<D>(kl) >> 1;                     // same for kl + 16
+                const uint32_t vrow = (uint32_t)(uintptr_t)(SPECVLM_AS3 const void*)(vt_lds + kl * ROW_BYTES + (r & 3) * 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int kl = chunk * kChunkKeys + (i < 4 ? 4 * c + i : 16 + 4 * c + (i - 4));
-                vr[i] = *reinterpret_cast<const vvec_t*>(vt_lds + kl * ROW_BYTES + r * (DJ * 2));
+                for (int j = 0; j < DJ; ++j) {
+                    const uint32_t src = vrow + (uint32_t)((j ^ pair_swz) * 32);
+                    const u32x2 lo = lds_read_tr16<0>(src);
+                    const u32x2 hi = lds_read_tr16<16 * ROW_BYTES>(src);
+                    vf[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
+                }
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
                              fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -322,15 +364,9 @@ void attn_split_kernel(const AttnParams p)
                 for (int j = 0; j < DJ; ++j) o_acc[j] *= alpha;
             }
             // ---- O^T += V^T P^T ----
+            lds_wait_fragments(vf);
 #pragma unroll
-            for (int j = 0; j < DJ; ++j) {
-                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 vt;
-#pragma unroll
-                for (int pr = 0; pr < 4; ++pr)
-                    vt[pr] = __builtin_amdgcn_perm(vr[2 * pr + 1][j >> 1], vr[2 * pr][j >> 1], sel);
-                o_acc[j] = mfma16(__builtin_bit_cast(bf16x8, vt), pf, o_acc[j]);
-            }
+            for (int j = 0; j < DJ; ++j) o_acc[j] = mfma16(vf[j], pf, o_acc[j]);
         }
     };
 
@@ -375,30 +411,21 @@ void attn_split_kernel(const AttnParams p)
     const int t_row = row / p.group, h_row = g * p.group + row % p.group;
     const int64_t slot = slot0 + row;
     if constexpr (KS == 1) {
-        // lane (r, c) holds columns (4c+i)*DJ + j of its row: write them out directly
+        // lane (r, c) holds columns 16j + 4c .. 16j + 4c + 3 of its row in o_acc[j]: write them out directly
         if (direct) {
             if (row >= n_rows) return;
             const float inv = 1.f / l_run;
-            __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head;
+            __bf16* op = p.out + (int64_t)(q0 + t_row) * p.q_tok + (int64_t)h_row * p.q_head + 4 * c;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
-                    x *= inv;
-                    *reinterpret_cast<bf16x4*>(op + (4 * c + i) * DJ + 4 * jj) = __builtin_convertvector(x, bf16x4);
-                }
+            for (int j = 0; j < DJ; ++j)
+                *reinterpret_cast<bf16x4*>(op + 16 * j) = __builtin_convertvector(o_acc[j] * inv, bf16x4);
             if (p.lse && c == 0)
                 p.lse[(int64_t)(q0 + t_row) * p.n_q_heads + h_row] = (m_run + fast_log2(l_run)) * kLn2;
         } else {
-            __bf16* po = p.part_o + slot * D;
+            __bf16* po = p.part_o + slot * D + 4 * c;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
-                    *reinterpret_cast<bf16x4*>(po + (4 * c + i) * DJ + 4 * jj) = __builtin_convertvector(x, bf16x4);
-                }
+            for (int j = 0; j < DJ; ++j)
+                *reinterpret_cast<bf16x4*>(po + 16 * j) = __builtin_convertvector(o_acc[j], bf16x4);
             if (c == 0) { p.part_ml[slot * 2] = m_run; p.part_ml[slot * 2 + 1] = l_run; }
         }
     } else {
@@ -419,15 +446,9 @@ void attn_split_kernel(const AttnParams p)
         const float f = fast_exp2(m_run - ((m_all == -INFINITY) ? 0.f : m_all));
         if (c == 0) sm_l[wave * 16 + r] = l_run * f;
         {
-            float* buf = sm_o + (wave * 16 + r) * LDS_STRIDE;
+            float* buf = sm_o + (wave * 16 + r) * LDS_STRIDE + 4 * c;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DJ / 4; ++jj) {
-                    floatx4 x = {o_acc[4 * jj][i], o_acc[4 * jj + 1][i], o_acc[4 * jj + 2][i], o_acc[4 * jj + 3][i]};
-                    x *= f;
-                    *reinterpret_cast<floatx4*>(buf + (4 * c + i) * DJ + 4 * jj) = x;
-                }
+            for (int j = 0; j < DJ; ++j) *reinterpret_cast<floatx4*>(buf + 16 * j) = o_acc[j] * f;
         }
         __syncthreads();
         float l_all = 0.f;
@@ -710,7 +731,8 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int n_rgroups, i
         // busy; more, smaller splits only add partial results and rounds (measured on 8 kv heads:
         // 131K keys run at 6.2 TB/s with 24 or 32 splits per head, 4.7 TB/s with 128; 33K keys at
         // 4.9 TB/s with 24, 4.2 TB/s with 32).
-        s = (kTargetWorkgroups + heads - 1) / heads;
+        // (with several row groups per head the sweep is bound by arithmetic, not HBM: every CU gets a workgroup)
+        s = ((n_rgroups > 1 ? kNumCu : kTargetWorkgroups) + heads - 1) / heads;
         if (batch > 1) {
             // Batches too large for the balanced decomposition: cap a split at 2048 keys so that
             // long and short requests decompose into similar pieces the dispatcher can balance,
