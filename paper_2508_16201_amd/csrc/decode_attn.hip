@@ -288,6 +288,9 @@ void attn_split_kernel(const AttnParams p)
 #pragma unroll
     for (int j = 0; j < DJ; ++j) o_acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+    // (a zero scale is taken as a vanishing one, so that a masked logit, -inf, times the scale stays -inf
+    // instead of becoming NaN; every other logit still scales to 0)
+    const float sc = fmaxf(p.scale_log2, 1e-30f);
     auto compute_tile = [&](int tile, int stage) {
         const unsigned char* kt_lds = smem + stage * (2 * TILE_BYTES);
         const unsigned char* vt_lds = kt_lds + TILE_BYTES;
@@ -310,9 +313,11 @@ void attn_split_kernel(const AttnParams p)
                 s0 = mfma16(__builtin_bit_cast(bf16x8, k0), qf[kk], s0);
                 s1 = mfma16(__builtin_bit_cast(bf16x8, k1), qf[kk], s1);
             }
+            // The logits stay unscaled: the scale (> 0) is applied to the maximum once and rides in the
+            // fused multiply-add that forms each exponent.
             float s[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { s[i] = s0[i] * p.scale_log2; s[4 + i] = s1[i] * p.scale_log2; }
+            for (int i = 0; i < 4; ++i) { s[i] = s0[i]; s[4 + i] = s1[i]; }
             if (need_mask) {
                 // Block keys this lane's query row may see (bit b = block key b).  Chain: the block is
                 // causal, query t sees block keys 0..t; tree: the caller's ancestor mask, fetched here
@@ -347,7 +352,7 @@ void attn_split_kernel(const AttnParams p)
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
                              fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-            mx = quad_max(mx);
+            mx = quad_max(mx) * sc;
             const float m_new = fmaxf(m_run, mx);
             const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run - m_ref);
@@ -356,7 +361,7 @@ void attn_split_kernel(const AttnParams p)
             floatx8 pv;
             float psum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(s[i] - m_ref); psum += pv[i]; }
+            for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(fmaf(s[i], sc, -m_ref)); psum += pv[i]; }
             l_run = l_run * alpha + psum;
             const bf16x8 pf = __builtin_convertvector(pv, bf16x8);
             if (__any(rescale)) {
@@ -731,8 +736,10 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int n_rgroups, i
         // busy; more, smaller splits only add partial results and rounds (measured on 8 kv heads:
         // 131K keys run at 6.2 TB/s with 24 or 32 splits per head, 4.7 TB/s with 128; 33K keys at
         // 4.9 TB/s with 24, 4.2 TB/s with 32).
-        // (with several row groups per head the sweep is bound by arithmetic, not HBM: every CU gets a workgroup)
-        s = ((n_rgroups > 1 ? kNumCu : kTargetWorkgroups) + heads - 1) / heads;
+        s = (kTargetWorkgroups + heads - 1) / heads;
+        // (with several row groups per head the sweep is bound by arithmetic, not HBM: as many workgroups
+        // as fit in one round on the 256 CUs, never one more)
+        if (n_rgroups > 1) s = kNumCu / heads;
         if (batch > 1) {
             // Batches too large for the balanced decomposition: cap a split at 2048 keys so that
             // long and short requests decompose into similar pieces the dispatcher can balance,
