@@ -193,11 +193,13 @@ __device__ __forceinline__ void lds_wait_fragments(bf16x8 (&f)[N])
         __asm__ volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
 }
 
+constexpr int kLoaderWaves = 4;      // waves of a workgroup that only issue the direct-to-LDS loads
+
 template <int D, int MB, int KS, int TK, int NS, bool STREAM>
-__global__ __launch_bounds__(MB * KS * kWave)
+__global__ __launch_bounds__((MB * KS + kLoaderWaves) * kWave)
 void attn_split_kernel(const AttnParams p)
 {
-    constexpr int NW = MB * KS;                  // waves per workgroup
+    constexpr int NW = MB * KS;                  // compute waves per workgroup (the loader waves come after them)
     constexpr int DJ = D / 16;                   // value columns per lane (8 or 4)
     constexpr int KK = D / 32;                   // MFMA steps over the head dimension
     constexpr int CH = D / 8;                    // 16-byte chunks per key row
@@ -206,8 +208,9 @@ void attn_split_kernel(const AttnParams p)
     constexpr int TILE_BYTES = TK * ROW_BYTES;   // one of K or V
     constexpr int LOADS_PER_MAT = TK / KEYS_PER_LOAD;
     constexpr int LOADS = 2 * LOADS_PER_MAT;     // wave-wide loads per stage (K then V)
-    constexpr int LW = largest_divisor_le(LOADS, NW);   // waves that issue loads
+    constexpr int LW = kLoaderWaves;             // waves that issue loads
     constexpr int LPW = LOADS / LW;              // loads per loader wave per stage
+    static_assert(LOADS % LW == 0, "the loads of a stage must divide among the loader waves");
     constexpr int NCHUNK = TK / kChunkKeys;      // 32-key chunks per tile
     constexpr int LDS_STRIDE = D + 4;            // merge buffer row stride (floats)
     static_assert(NCHUNK % KS == 0, "chunks must divide among the key-split waves");
@@ -215,7 +218,9 @@ void attn_split_kernel(const AttnParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int mb = wave % MB, ks = wave / MB;
+    const bool is_loader = wave >= NW;
+    const int lw = wave - NW;                    // loader index
+    const int mb = wave % MB, ks = wave / MB;    // (compute waves)
     const int r = lane & 15, c = lane >> 4;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -238,7 +243,7 @@ void attn_split_kernel(const AttnParams p)
     int t_blk;                  // this lane's query row is the block's t_blk-th query
     unsigned char* q_stage = smem + (NS - 1) * (2 * TILE_BYTES) + wave * (KK * 1024);
     static_assert(MB * KS * KK * 1024 <= 2 * TILE_BYTES, "Q staging must fit in one ring stage");
-    {
+    if (!is_loader) {
         const int row = row0 + mb * 16 + r;
         const bool live = row < n_rows;             // padding rows read row 0: finite, never stored
         const int t = live ? row / p.group : 0;
@@ -264,7 +269,7 @@ void attn_split_kernel(const AttnParams p)
         unsigned char* st = smem + stage * (2 * TILE_BYTES);
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
-            const int n = wave + LW * j;
+            const int n = lw + LW * j;
             const bool is_v = n >= LOADS_PER_MAT;
             const int kl = (is_v ? n - LOADS_PER_MAT : n) * KEYS_PER_LOAD + ld_key;   // key inside the tile
             // rows past the split's end are masked in the compute: re-read its last row
@@ -379,38 +384,42 @@ void attn_split_kernel(const AttnParams p)
     // The loader waves always start NS-1 tiles (a split shorter than that loads its last tile
     // again into a stage nobody reads), then every wave waits for its Q fragments, which are older
     // than any tile load, and takes them into registers.
-    const bool is_loader = wave < LW;
     const int n_tiles = (k_end - k_begin + TK - 1) / TK;            // >= 1
     const int n_load = n_tiles > NS - 1 ? n_tiles : NS - 1;          // tiles as the loader counts them
+    // Two loops, one per role (their registers do not add up); both pass the same barrier once per tile.
     if (is_loader) {
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) issue_tile(s < n_tiles ? s : n_tiles - 1, s);
-        wait_vmcnt<(NS - 1) * LPW>();                // the Q loads are older than every tile load
+        int i = 0;
+        do {
+            // tiles issued after tile i so far: min(NS-2, n_load-1-i); each is LPW loads of a loader wave
+            const int younger = min(NS - 2, n_load - 1 - i);
+            wait_vmcnt<(NS - 2) * LPW>();
+            if constexpr (NS >= 5) { if (younger <= 2) wait_vmcnt<2 * LPW>(); }
+            if constexpr (NS >= 4) { if (younger <= 1) wait_vmcnt<1 * LPW>(); }
+            if constexpr (NS >= 3) { if (younger <= 0) wait_vmcnt<0>(); }
+            stage_barrier();                         // tile i landed for everyone; stage (i-1)%NS is free
+            if (i + NS - 1 < n_load) issue_tile(i + NS - 1, (i + NS - 1) % NS);
+        } while (++i < n_tiles);
+        wait_vmcnt<0>();                             // (a short split's spare copies may still be landing)
     } else {
-        wait_vmcnt<0>();
-    }
-    __asm__ volatile("" ::: "memory");
+        wait_vmcnt<0>();                             // a compute wave's only loads: its Q fragments
+        __asm__ volatile("" ::: "memory");
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-        qf[kk] = *reinterpret_cast<const bf16x8*>(q_stage + kk * 1024 + lane * 16);
-    __asm__ volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): read before the stage is handed to the loader
-    __asm__ volatile("" ::: "memory");
-    int i = 0;
-    do {
-        // tiles issued after tile i so far: min(NS-2, n_load-1-i); each is LPW loads of a loader wave
-        const int younger = min(NS - 2, n_load - 1 - i);
-        wait_vmcnt<(NS - 2) * LPW>();
-        if constexpr (NS >= 5) { if (younger <= 2) wait_vmcnt<2 * LPW>(); }
-        if constexpr (NS >= 4) { if (younger <= 1) wait_vmcnt<1 * LPW>(); }
-        if constexpr (NS >= 3) { if (younger <= 0) wait_vmcnt<0>(); }
-        stage_barrier();                             // tile i landed for everyone; stage (i-1)%NS is free
-        if (is_loader && i + NS - 1 < n_load) issue_tile(i + NS - 1, (i + NS - 1) % NS);
-        compute_tile(i, i % NS);
-    } while (++i < n_tiles);
-    wait_vmcnt<0>();                                 // (a short split's spare copies may still be landing)
+        for (int kk = 0; kk < KK; ++kk)
+            qf[kk] = *reinterpret_cast<const bf16x8*>(q_stage + kk * 1024 + lane * 16);
+        __asm__ volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): read before the stage is handed to the loaders
+        __asm__ volatile("" ::: "memory");
+        int i = 0;
+        do {
+            stage_barrier();
+            compute_tile(i, i % NS);
+        } while (++i < n_tiles);
+    }
 
-    // ---- epilogue ----
+    // ---- epilogue (the loader waves only keep the barriers of the exchange) ----
+    if constexpr (KS == 1) { if (is_loader) return; }
     l_run = quad_sum(l_run);
     const int row = row0 + mb * 16 + r;
     const int t_row = row / p.group, h_row = g * p.group + row % p.group;
@@ -443,19 +452,20 @@ void attn_split_kernel(const AttnParams p)
         float* sm_m = reinterpret_cast<float*>(smem);            // [NW][16]
         float* sm_l = sm_m + NW * 16;                            // [NW][16]
         float* sm_o = sm_l + NW * 16;                            // [NW][16][LDS_STRIDE]
-        if (c == 0) sm_m[wave * 16 + r] = m_run;
+        if (c == 0 && !is_loader) sm_m[wave * 16 + r] = m_run;
         __syncthreads();
         float m_all = m_run;
 #pragma unroll
         for (int kx = 0; kx < KS; ++kx) m_all = fmaxf(m_all, sm_m[(kx * MB + mb) * 16 + r]);
         const float f = fast_exp2(m_run - ((m_all == -INFINITY) ? 0.f : m_all));
-        if (c == 0) sm_l[wave * 16 + r] = l_run * f;
-        {
+        if (c == 0 && !is_loader) sm_l[wave * 16 + r] = l_run * f;
+        if (!is_loader) {
             float* buf = sm_o + (wave * 16 + r) * LDS_STRIDE + 4 * c;
 #pragma unroll
             for (int j = 0; j < DJ; ++j) *reinterpret_cast<floatx4*>(buf + 16 * j) = o_acc[j] * f;
         }
         __syncthreads();
+        if (is_loader) return;
         float l_all = 0.f;
 #pragma unroll
         for (int kx = 0; kx < KS; ++kx) l_all += sm_l[(kx * MB + mb) * 16 + r];
@@ -525,7 +535,7 @@ void attn_split_kernel(const AttnParams p)
         // the merge kernel's view of the decomposition: for every (request, head) its first partial
         // slot and the number of pieces (the groups that touch a request are consecutive; the group
         // that owns unit x is the largest j with j*T/G <= x)
-        for (int seg = threadIdx.x; seg < p.batch * H; seg += MB * KS * kWave) {
+        for (int seg = threadIdx.x; seg < p.batch * H; seg += (MB * KS + kLoaderWaves) * kWave) {
             const int sb = seg / H, sg = seg % H;
             int64_t first = 0;
             for (int bb = 0; bb < sb; ++bb) first += attn_request_tiles(p, bb, TK);
@@ -779,7 +789,7 @@ static int launch_attn_s(const AttnParams& p, hipStream_t stream)
             raised[dev].store(true, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, STREAM>), dim3(p.n_work), dim3(NW * kWave),
+    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, STREAM>), dim3(p.n_work), dim3((NW + kLoaderWaves) * kWave),
                        lds, stream, p);
     return launch_status();
 }
