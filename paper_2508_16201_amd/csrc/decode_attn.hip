@@ -6,15 +6,20 @@
 //   One workgroup owns one (request, kv head, key split).  All G*q_len query
 //   rows that share the kv head are packed into MFMA row blocks of 16 (MB of
 //   them, MB <= 4), so every K/V byte is read from HBM exactly once.  The
-//   workgroup has MB*KS waves: wave (mb, ks) owns row block mb and every KS-th
-//   32-key chunk of each tile, so a wave carries one 16-row accumulator only.
+//   workgroup has MB*KS compute waves -- wave (mb, ks) owns row block mb and
+//   every KS-th 32-key chunk of each tile, so a wave carries one 16-row
+//   accumulator only -- and four loader waves that do nothing but issue the
+//   tile loads: a direct-to-LDS load of 1 KB holds its wave for about 70 cycles,
+//   eight of them per tile are a quarter of a tile's time when the waves that
+//   compute have to issue them.
 //
 // Data movement
 //   K/V tiles of TK keys stream HBM -> LDS with direct-to-LDS loads
 //   (global_load_lds_dwordx4: no registers in between) into a ring of NS
 //   stages; NS-1 tiles are in flight while one is consumed.  A stage is
-//   released by one s_barrier per tile; the waves wait on their own vmcnt for
-//   the tile they are about to read, never on the younger tiles.  K rows are
+//   released by one s_barrier per tile, which all waves pass; before it the
+//   loader waves wait on their own vmcnt for the tile about to be read, never
+//   on the younger tiles.  K rows are
 //   stored with their 16-byte chunks XOR-swizzled by the key index so that the
 //   MFMA operand reads (16 keys x one chunk per 16 lanes) hit distinct banks;
 //   the swizzle is applied on the global-address side, the LDS side of a
