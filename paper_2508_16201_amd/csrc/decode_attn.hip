@@ -8,10 +8,10 @@
 //   them, MB <= 4), so every K/V byte is read from HBM exactly once.  The
 //   workgroup has MB*KS compute waves -- wave (mb, ks) owns row block mb and
 //   every KS-th 32-key chunk of each tile, so a wave carries one 16-row
-//   accumulator only -- and four loader waves that do nothing but issue the
-//   tile loads: a direct-to-LDS load of 1 KB holds its wave for about 70 cycles,
-//   eight of them per tile are a quarter of a tile's time when the waves that
-//   compute have to issue them.
+//   accumulator only -- and, in the multi-query shapes, four loader waves that
+//   do nothing but issue the tile loads: a direct-to-LDS load of 1 KB holds its
+//   wave for about 70 cycles, eight of them per tile are a quarter of a tile's
+//   time when the waves that compute have to issue them.
 //
 // Data movement
 //   K/V tiles of TK keys stream HBM -> LDS with direct-to-LDS loads
@@ -198,13 +198,13 @@ __device__ __forceinline__ void lds_wait_fragments(bf16x8 (&f)[N])
         __asm__ volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
 }
 
-constexpr int kLoaderWaves = 4;      // waves of a workgroup that only issue the direct-to-LDS loads
-
-template <int D, int MB, int KS, int TK, int NS, bool STREAM>
-__global__ __launch_bounds__((MB * KS + kLoaderWaves) * kWave)
+// NLD: waves of a workgroup that only issue the direct-to-LDS loads (0: the compute waves issue them)
+template <int D, int MB, int KS, int TK, int NS, int NLD, bool STREAM>
+__global__ __launch_bounds__((MB * KS + NLD) * kWave)
 void attn_split_kernel(const AttnParams p)
 {
     constexpr int NW = MB * KS;                  // compute waves per workgroup (the loader waves come after them)
+    constexpr bool SPLIT_ROLES = NLD > 0;
     constexpr int DJ = D / 16;                   // value columns per lane (8 or 4)
     constexpr int KK = D / 32;                   // MFMA steps over the head dimension
     constexpr int CH = D / 8;                    // 16-byte chunks per key row
@@ -213,7 +213,7 @@ void attn_split_kernel(const AttnParams p)
     constexpr int TILE_BYTES = TK * ROW_BYTES;   // one of K or V
     constexpr int LOADS_PER_MAT = TK / KEYS_PER_LOAD;
     constexpr int LOADS = 2 * LOADS_PER_MAT;     // wave-wide loads per stage (K then V)
-    constexpr int LW = kLoaderWaves;             // waves that issue loads
+    constexpr int LW = SPLIT_ROLES ? NLD : largest_divisor_le(LOADS, NW);   // waves that issue loads
     constexpr int LPW = LOADS / LW;              // loads per loader wave per stage
     static_assert(LOADS % LW == 0, "the loads of a stage must divide among the loader waves");
     constexpr int NCHUNK = TK / kChunkKeys;      // 32-key chunks per tile
@@ -223,8 +223,9 @@ void attn_split_kernel(const AttnParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool is_loader = wave >= NW;
-    const int lw = wave - NW;                    // loader index
+    const bool is_loader = SPLIT_ROLES ? wave >= NW : wave < LW;
+    const bool computes = SPLIT_ROLES ? wave < NW : true;
+    const int lw = SPLIT_ROLES ? wave - NW : wave;   // loader index
     const int mb = wave % MB, ks = wave / MB;    // (compute waves)
     const int r = lane & 15, c = lane >> 4;
 
@@ -248,7 +249,7 @@ void attn_split_kernel(const AttnParams p)
     int t_blk;                  // this lane's query row is the block's t_blk-th query
     unsigned char* q_stage = smem + (NS - 1) * (2 * TILE_BYTES) + wave * (KK * 1024);
     static_assert(MB * KS * KK * 1024 <= 2 * TILE_BYTES, "Q staging must fit in one ring stage");
-    if (!is_loader) {
+    if (computes) {
         const int row = row0 + mb * 16 + r;
         const bool live = row < n_rows;             // padding rows read row 0: finite, never stored
         const int t = live ? row / p.group : 0;
@@ -391,6 +392,7 @@ void attn_split_kernel(const AttnParams p)
     // than any tile load, and takes them into registers.
     const int n_tiles = (k_end - k_begin + TK - 1) / TK;            // >= 1
     const int n_load = n_tiles > NS - 1 ? n_tiles : NS - 1;          // tiles as the loader counts them
+    if constexpr (SPLIT_ROLES) {
     // Two loops, one per role (their registers do not add up); both pass the same barrier once per tile.
     if (is_loader) {
 #pragma unroll
@@ -422,9 +424,40 @@ void attn_split_kernel(const AttnParams p)
             compute_tile(i, i % NS);
         } while (++i < n_tiles);
     }
+    } else {
+    // Every wave computes and the first LW of them also issue the loads.  The loader waves always start
+    // NS-1 tiles, then every wave waits for its Q fragments, which are older than any tile load.
+    if (is_loader) {
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue_tile(s < n_tiles ? s : n_tiles - 1, s);
+        wait_vmcnt<(NS - 1) * LPW>();                // the Q loads are older than every tile load
+    } else {
+        wait_vmcnt<0>();
+    }
+    __asm__ volatile("" ::: "memory");
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(q_stage + kk * 1024 + lane * 16);
+    __asm__ volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): read before the stage is handed to the loader
+    __asm__ volatile("" ::: "memory");
+    int i = 0;
+    do {
+        // tiles issued after tile i so far: min(NS-2, n_load-1-i); each is LPW loads of a loader wave
+        const int younger = min(NS - 2, n_load - 1 - i);
+        wait_vmcnt<(NS - 2) * LPW>();
+        if constexpr (NS >= 5) { if (younger <= 2) wait_vmcnt<2 * LPW>(); }
+        if constexpr (NS >= 4) { if (younger <= 1) wait_vmcnt<1 * LPW>(); }
+        if constexpr (NS >= 3) { if (younger <= 0) wait_vmcnt<0>(); }
+        stage_barrier();                             // tile i landed for everyone; stage (i-1)%NS is free
+        if (is_loader && i + NS - 1 < n_load) issue_tile(i + NS - 1, (i + NS - 1) % NS);
+        compute_tile(i, i % NS);
+    } while (++i < n_tiles);
+    wait_vmcnt<0>();                                 // (a short split's spare copies may still be landing)
+    }
 
     // ---- epilogue (the loader waves only keep the barriers of the exchange) ----
-    if constexpr (KS == 1) { if (is_loader) return; }
+    if constexpr (KS == 1) { if (!computes) return; }
     l_run = quad_sum(l_run);
     const int row = row0 + mb * 16 + r;
     const int t_row = row / p.group, h_row = g * p.group + row % p.group;
@@ -457,20 +490,20 @@ void attn_split_kernel(const AttnParams p)
         float* sm_m = reinterpret_cast<float*>(smem);            // [NW][16]
         float* sm_l = sm_m + NW * 16;                            // [NW][16]
         float* sm_o = sm_l + NW * 16;                            // [NW][16][LDS_STRIDE]
-        if (c == 0 && !is_loader) sm_m[wave * 16 + r] = m_run;
+        if (c == 0 && computes) sm_m[wave * 16 + r] = m_run;
         __syncthreads();
         float m_all = m_run;
 #pragma unroll
         for (int kx = 0; kx < KS; ++kx) m_all = fmaxf(m_all, sm_m[(kx * MB + mb) * 16 + r]);
         const float f = fast_exp2(m_run - ((m_all == -INFINITY) ? 0.f : m_all));
-        if (c == 0 && !is_loader) sm_l[wave * 16 + r] = l_run * f;
-        if (!is_loader) {
+        if (c == 0 && computes) sm_l[wave * 16 + r] = l_run * f;
+        if (computes) {
             float* buf = sm_o + (wave * 16 + r) * LDS_STRIDE + 4 * c;
 #pragma unroll
             for (int j = 0; j < DJ; ++j) *reinterpret_cast<floatx4*>(buf + 16 * j) = o_acc[j] * f;
         }
         __syncthreads();
-        if (is_loader) return;
+        if (!computes) return;
         float l_all = 0.f;
 #pragma unroll
         for (int kx = 0; kx < KS; ++kx) l_all += sm_l[(kx * MB + mb) * 16 + r];
@@ -540,7 +573,7 @@ void attn_split_kernel(const AttnParams p)
         // the merge kernel's view of the decomposition: for every (request, head) its first partial
         // slot and the number of pieces (the groups that touch a request are consecutive; the group
         // that owns unit x is the largest j with j*T/G <= x)
-        for (int seg = threadIdx.x; seg < p.batch * H; seg += (MB * KS + kLoaderWaves) * kWave) {
+        for (int seg = threadIdx.x; seg < p.batch * H; seg += (MB * KS + NLD) * kWave) {
             const int sb = seg / H, sg = seg % H;
             int64_t first = 0;
             for (int bb = 0; bb < sb; ++bb) first += attn_request_tiles(p, bb, TK);
@@ -775,7 +808,7 @@ static int choose_splits(int batch, int kv_len, int n_kv_heads, int n_rgroups, i
     return s;
 }
 
-template <int D, int MB, int KS, int TK, int NS, bool STREAM>
+template <int D, int MB, int KS, int TK, int NS, int NLD, bool STREAM>
 static int launch_attn_s(const AttnParams& p, hipStream_t stream)
 {
     constexpr int NW = MB * KS;
@@ -788,13 +821,13 @@ static int launch_attn_s(const AttnParams& p, hipStream_t stream)
         int dev = -1;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECVLM_ELAUNCH;
         if (!raised[dev].load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS, STREAM>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_split_kernel<D, MB, KS, TK, NS, NLD, STREAM>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return SPECVLM_ELAUNCH;
             raised[dev].store(true, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, STREAM>), dim3(p.n_work), dim3((NW + kLoaderWaves) * kWave),
+    hipLaunchKernelGGL((attn_split_kernel<D, MB, KS, TK, NS, NLD, STREAM>), dim3(p.n_work), dim3((NW + NLD) * kWave),
                        lds, stream, p);
     return launch_status();
 }
@@ -804,25 +837,27 @@ static int launch_attn_s(const AttnParams& p, hipStream_t stream)
 // Smaller caches (a draft's pruned cache, re-read at every decode step) stay cacheable.
 constexpr int64_t kStreamBytes = 8ll << 20;
 
-template <int D, int MB, int KS, int TK, int NS>
+template <int D, int MB, int KS, int TK, int NS, int NLD>
 static int launch_attn(const AttnParams& p, hipStream_t stream)
 {
     const int64_t kv_bytes = 2ll * p.batch * p.n_kv_heads * (int64_t)p.kv_len * D * 2;
-    return kv_bytes >= kStreamBytes ? launch_attn_s<D, MB, KS, TK, NS, true>(p, stream)
-                                    : launch_attn_s<D, MB, KS, TK, NS, false>(p, stream);
+    return kv_bytes >= kStreamBytes ? launch_attn_s<D, MB, KS, TK, NS, NLD, true>(p, stream)
+                                    : launch_attn_s<D, MB, KS, TK, NS, NLD, false>(p, stream);
 }
 
 template <int D>
 static int launch_attn_d(const AttnParams& p, int mb, hipStream_t stream)
 {
 
-    // (key-split waves, tile keys, ring depth) per row-block count; the ring
-    // holds NS * 2 * TK * D * 2 bytes of LDS.
+    // (key-split waves, tile keys, ring depth, loader waves) per row-block count; the ring
+    // holds NS * 2 * TK * D * 2 bytes of LDS.  The single-query decode keeps its four waves (loading and
+    // computing): on the draft's small cache the four extra waves cost more at workgroup start-up than
+    // they save (6.7 against 6.4 us per layer).
     switch (mb) {
-        case 1: return launch_attn<D, 1, 4, 128, 2>(p, stream);
-        case 2: return launch_attn<D, 2, 2, 64, 3>(p, stream);
-        case 3: return launch_attn<D, 3, 2, 64, 3>(p, stream);
-        case 4: return launch_attn<D, 4, 2, 64, 3>(p, stream);
+        case 1: return launch_attn<D, 1, 4, 128, 2, 0>(p, stream);
+        case 2: return launch_attn<D, 2, 2, 64, 3, 4>(p, stream);
+        case 3: return launch_attn<D, 3, 2, 64, 3, 4>(p, stream);
+        case 4: return launch_attn<D, 4, 2, 64, 3, 4>(p, stream);
     }
     return SPECVLM_EUNSUPPORTED;
 }
