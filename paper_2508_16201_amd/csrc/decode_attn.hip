@@ -112,6 +112,7 @@ __device__ __forceinline__ AttnBalance attn_balance(const AttnParams& p, int til
     return r;
 }
 constexpr int kMaxSplits = 256;
+constexpr float kSumRedo = 0x1p100f;     // a lane's sum of one chunk at or above this (or NaN) is redone with the maximum tracked
 constexpr int kMaxQueryBlock = 64;      // queries per request: a row's view of its block is one 64-bit mask
 constexpr int kMaxDevices = 64;         // per-device host state (kernel attributes, scratch addresses)
 constexpr int kTargetWorkgroups = 192;  // workgroups of a single-request launch
@@ -361,24 +362,42 @@ void attn_split_kernel(const AttnParams p)
                     vf[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
                 }
             }
-            float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
-                             fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-            mx = quad_max(mx) * sc;
-            const float m_new = fmaxf(m_run, mx);
-            const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run - m_ref);
-            const bool rescale = m_new != m_run;
-            m_run = m_new;
+            // Away from the mask the running maximum is not tracked: the exponentials are taken against
+            // the reference the earlier chunks left (a logit above it only makes its term larger than one),
+            // which saves the maximum, its exchange over the quarter waves and the rescale test -- a
+            // quarter of a chunk's VALU work.  A lane sum that is no longer a moderate finite number (a
+            // logit 2^100 above the reference, or a reference not set yet) sends the wave through the
+            // tracked form of the same chunk instead.
             floatx8 pv;
-            float psum = 0.f;
+            bool settled = false;
+            if (!need_mask && !__any(!(m_run > -INFINITY))) {
+                float psum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(fmaf(s[i], sc, -m_ref)); psum += pv[i]; }
-            l_run = l_run * alpha + psum;
-            const bf16x8 pf = __builtin_convertvector(pv, bf16x8);
-            if (__any(rescale)) {
-#pragma unroll
-                for (int j = 0; j < DJ; ++j) o_acc[j] *= alpha;
+                for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(fmaf(s[i], sc, -m_run)); psum += pv[i]; }
+                if (!__any(!(psum < kSumRedo))) {
+                    l_run += psum;
+                    settled = true;
+                }
             }
+            if (!settled) {
+                float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])),
+                                 fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+                mx = quad_max(mx) * sc;
+                const float m_new = fmaxf(m_run, mx);
+                const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = fast_exp2(m_run - m_ref);
+                const bool rescale = m_new != m_run;
+                m_run = m_new;
+                float psum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { pv[i] = fast_exp2(fmaf(s[i], sc, -m_ref)); psum += pv[i]; }
+                l_run = l_run * alpha + psum;
+                if (__any(rescale)) {
+#pragma unroll
+                    for (int j = 0; j < DJ; ++j) o_acc[j] *= alpha;
+                }
+            }
+            const bf16x8 pf = __builtin_convertvector(pv, bf16x8);
             // ---- O^T += V^T P^T ----
             lds_wait_fragments(vf);
 #pragma unroll

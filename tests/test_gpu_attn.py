@@ -70,6 +70,35 @@ def test_matches_oracle(B, q_len, kv_len, hq, hkv, d, splits):
     run_case(B, q_len, kv_len, hq, hkv, d, seed=100 + q_len + kv_len, num_splits=splits)
 
 
+@pytest.mark.parametrize("splits", [0, 1, 5])
+@pytest.mark.parametrize("bumps", [((1000, 60.0),), ((1500, 150.0),), ((500, 60.0), (2000, 150.0), (2600, 40.0)),
+                                   ((70, 120.0), (2990, 90.0))])
+def test_dominant_keys_late_in_the_cache(B, splits, bumps):
+    """Keys whose logits tower over everything before them (by 2^40 .. 2^150 in the softmax's own base-2
+    units): away from the mask the kernel takes exponentials against the reference left by earlier
+    chunks instead of tracking the maximum, and must fall back to the tracked form when a term no
+    longer fits; either way the result is the oracle's."""
+    from paper_2508_16201_amd.synth import f32_to_bf16_bits, bf16_bits_to_f32
+    q_len, kv_len, hq, hkv, d, scale = 6, 3000, 16, 2, 128, 0.088
+    rng = np.random.default_rng(4242 + len(bumps) + int(bumps[0][1]))
+    base = rng.standard_normal(d).astype(np.float32)
+    qf = base[None, None, :] + 0.3 * rng.standard_normal((q_len, hq, d)).astype(np.float32)   # rows nearly parallel
+    kf = 0.2 * rng.standard_normal((kv_len, hkv, d)).astype(np.float32)
+    vf = rng.standard_normal((kv_len, hkv, d)).astype(np.float32)
+    unit = base / np.linalg.norm(base)
+    for pos, log2_units in bumps:
+        # logit (base-2 units) of a query row ~ scale * log2(e) * alpha * |base|
+        alpha = log2_units / (scale * np.log2(np.e) * np.linalg.norm(base))
+        kf[pos] = alpha * unit[None, :]
+    q, k, v = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf), f32_to_bf16_bits(vf)
+    want, want_lse = oracle.decode_attn(q, k, v, scale)
+    out, lse = B.decode_attn(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, want_lse=True, num_splits=splits)
+    torch.cuda.synchronize()
+    tag = f"bumps {bumps} splits {splits}"
+    assert_attn_close(out, want, tag)
+    np.testing.assert_allclose(host_f64(lse), want_lse, atol=2e-3, rtol=1e-4, err_msg=tag)
+
+
 def test_head_major_cache_layout(B):
     run_case(B, 6, 2500, 16, 2, 128, seed=7, head_major=True)
     run_case(B, 1, 900, 8, 2, 64, seed=8, head_major=True, num_splits=3)
