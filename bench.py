@@ -317,9 +317,9 @@ def main():
                    "score_row_lse": "supplied (torch logsumexp at set-up, untimed)" if args.score_lse else "computed",
                    "launch": "eager" if args.eager else "hip-graph per stage"},
         "value_source": "verify_attn stage inside the timed steps (mean over steps)",
-        "in_step_note": "inside a step the verify stage starts within 1 ms of the score stage's 10 ms of matrix work, after "
-                        "which this chip runs the same graph about 1 us per layer slower for one replay (the isolated "
-                        "figure beside it is the same graph replayed back to back)",
+        "in_step_note": "inside a step the verify stage is the first pass over the 4.2 GB cache after the other stages ran; a "
+                        "pass that follows another pass over the same cache (the isolated figure beside it) is 0.5-1 us "
+                        "per layer faster; an idle gap after the score stage changes neither",
         "pct_of_hbm_peak": round(100.0 * attn_gbs["mean"] / HBM_PEAK_GBS, 1),
         "verify_attn_us_per_layer": {k: round(v, 3) for k, v in layer_us.items()},
         "verify_attn_gbs": {k: round(v, 1) for k, v in attn_gbs.items()},
