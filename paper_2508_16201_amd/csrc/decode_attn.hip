@@ -8,10 +8,11 @@
 //   them, MB <= 4), so every K/V byte is read from HBM exactly once.  The
 //   workgroup has MB*KS compute waves -- wave (mb, ks) owns row block mb and
 //   every KS-th 32-key chunk of each tile, so a wave carries one 16-row
-//   accumulator only -- and, in the multi-query shapes, four loader waves that
-//   do nothing but issue the tile loads: a direct-to-LDS load of 1 KB holds its
-//   wave for about 70 cycles, eight of them per tile are a quarter of a tile's
-//   time when the waves that compute have to issue them.
+//   accumulator only -- and, in the multi-query shapes, two or four loader
+//   waves that do nothing but issue the tile loads: a direct-to-LDS load of
+//   1 KB holds its wave for about 70 cycles, eight of them per tile are a
+//   quarter of a tile's time when the waves that compute have to issue them.
+//   More than 64 rows per kv head are cut into row groups, one workgroup each.
 //
 // Data movement
 //   K/V tiles of TK keys stream HBM -> LDS with direct-to-LDS loads
@@ -32,9 +33,11 @@
 // Placement
 //   Workgroup ids run over the kv heads fastest; ids are dealt to the 8 XCDs
 //   round-robin, so with 8 kv heads all splits of a head and the merge of that
-//   head share one XCD and its L2, where the fp32 partials stay between the
-//   two kernels.  A single request is cut into about 192 workgroups in one
-//   round (HBM saturates before every CU is busy); ragged batches into splits
+//   head share one XCD and its L2, where the partials (bf16 outputs, fp32
+//   maxima and sums) stay between the two kernels.  A single request is cut
+//   into about 192 workgroups in one round (HBM saturates before every CU is
+//   busy); ragged batches of up to 64 requests into balanced pieces (equal runs
+//   of key tiles per group of workgroups, see below), larger ones into splits
 //   of at most 2048 keys that the dispatcher can balance.
 //
 // MFMA formulation (v_mfma_f32_16x16x32_bf16, lane = 16*c + r)
@@ -49,7 +52,9 @@
 //     that read pattern like K rows are for theirs.  Step j yields value
 //     columns 16j..16j+15 (lane (r, c): columns 16j+4c..16j+4c+3 of row r).
 //     O^T keeps row r in lane column r too, so the running-max rescale is a
-//     per-lane multiply.
+//     per-lane multiply -- and away from the mask no maximum is tracked at all
+//     (exponentials against the reference the earlier chunks left, with the
+//     tracked form as fallback; see compute_tile).
 #include <atomic>
 
 #include "common.h"
