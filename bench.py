@@ -402,6 +402,29 @@ def main():
             "gbs": round(big_bytes / (us_g * 1e-6) / 1e9, 1),
             "pct_of_hbm_peak": round(100.0 * big_bytes / (us_g * 1e-6) / 1e9 / HBM_PEAK_GBS, 1)}
         del big_k, big_v
+        # gather at the long-video configuration's sizes: 64 layers x 8 kv heads x d 128, 32 768 video + 256 text
+        # tokens, keep 10 / 25 / 50 % (1.85 / 4.4 / 8.7 GB read + written); uninitialised buffers (a row copy does
+        # not look at the values), kept rows = a seeded random subset in ascending order
+        w3g = synth.WORKLOADS["32b-long"]
+        L3, h3, d3, V3, n3ctx = w3g.n_layers, w3g.n_kv_heads, w3g.head_dim, w3g.n_video, w3g.n_ctx
+        src_k = torch.empty((L3, h3, n3ctx, d3), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
+        src_v = torch.empty_like(src_k)
+        gen3 = torch.Generator(device=dev); gen3.manual_seed(synth.SEED_BASE + 3100)
+        for pct in (10, 25, 50):
+            b3 = (V3 * pct + 50) // 100
+            keep3 = torch.randperm(V3, generator=gen3, device=dev)[:b3].sort().values.to(torch.int32)
+            rows3 = n3ctx - V3 + b3
+            dst_k = torch.empty((L3, h3, rows3, d3), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
+            dst_v = torch.empty_like(dst_k)
+            us3g = timed_replays(torch, graph_of(torch, lambda: B.gather_kv(src_k, src_v, 0, V3, keep3, k_dst=dst_k,
+                                                                            v_dst=dst_v), args.eager), 5)
+            bytes3 = 2 * 2 * L3 * rows3 * h3 * d3 * 2
+            other[f"gather 32b-long shape keep {pct}% ({L3} layers x {rows3} rows x {h3} kv heads d{d3})"] = {
+                "us": round(us3g, 1), "bytes_read_plus_written": bytes3,
+                "gbs": round(bytes3 / (us3g * 1e-6) / 1e9, 1),
+                "pct_of_hbm_peak": round(100.0 * bytes3 / (us3g * 1e-6) / 1e9 / HBM_PEAK_GBS, 1)}
+            del dst_k, dst_v, keep3
+        del src_k, src_v
         result["other_workloads"] = other
 
     if not args.no_cpu_baseline:
