@@ -10,12 +10,17 @@
 // One workgroup of 1024 threads per request; thread t owns the contiguous run
 // of tokens [t*per, (t+1)*per) and keeps their keys in registers, so every
 // "how many before me" question is one block-wide exclusive scan of popcounts.
+#include <atomic>
+
 #include "common.h"
 
 namespace specvlm {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelCopies = 64;            // copies of the digit histogram in LDS (summed after every pass)
+constexpr int kSelCopyWords = 257;        // a copy is 257 words long: the copies of one digit lie in different banks
+constexpr size_t kSelHistBytes = 2ull * kSelCopies * kSelCopyWords * sizeof(int);   // two sets: the passes alternate
 
 struct SelectParams {
     const float* scores;
@@ -37,6 +42,28 @@ __device__ __forceinline__ uint32_t score_key(float x)
     uint32_t u = __float_as_uint(x);
     if (x == 0.f) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// A thread's run of scores [first, first + per) of a request of n scores, four at a time (dword-aligned
+// 16-byte loads); slots past the run or past n read as 0.  With one score per load every instruction
+// would touch 64 different cache lines, and the address path takes a cycle per line: 13 such loads per
+// thread were the longest phase of the select kernel.
+template <int E>
+__device__ __forceinline__ void load_run(const float* sc, int first, int per, int n, float (&raw)[E])
+{
+    typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
+#pragma unroll
+    for (int e4 = 0; e4 < E; e4 += 4) {
+        const int idx = first + e4;
+        if (e4 + 3 < per && idx + 3 < n) {
+            const float4u v = *reinterpret_cast<const float4u*>(sc + idx);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) raw[e4 + i] = v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) raw[e4 + i] = (e4 + i < per && idx + i < n) ? sc[idx + i] : 0.f;
+        }
+    }
 }
 
 // Exclusive prefix sums of two ints per thread in one round of barriers.
@@ -64,8 +91,11 @@ template <int E>
 __global__ __launch_bounds__(kSelThreads)
 void select_kernel(const SelectParams p)
 {
-    __shared__ int s_hist[2][kSelWaves][257];    // per-wave histograms (padded: see below); the passes alternate between two sets
+    // kSelCopies copies of the digit histogram (padded: see below); the passes alternate between two sets
+    extern __shared__ int s_hist_dyn[];
+    int (*s_hist)[kSelCopies][kSelCopyWords] = reinterpret_cast<int (*)[kSelCopies][kSelCopyWords]>(s_hist_dyn);
     __shared__ int s_tot[256];
+    __shared__ int s_part[4][256];
     __shared__ int s_wave2[2][kSelWaves];
     __shared__ int s_pick[2];
 
@@ -79,13 +109,9 @@ void select_kernel(const SelectParams p)
     const int first = tid * per;
     const float* sc = p.scores + v0;
     float raw[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int idx = first + e;
-        raw[e] = (e < per && idx < n) ? sc[idx] : 0.f;
-    }
+    load_run<E>(sc, first, per, n, raw);
     // the first pass's histograms are cleared while the scores are on their way
-    for (int i = tid; i < kSelWaves * 257; i += kSelThreads) (&s_hist[0][0][0])[i] = 0;
+    for (int i = tid; i < kSelCopies * kSelCopyWords; i += kSelThreads) (&s_hist[0][0][0])[i] = 0;
     const int k = p.k_top[b], budget = p.keep_budget[b];
     const int out0 = p.cu_keep ? p.cu_keep[b] : 0;
     const bool bad = n < 0 || n > E * kSelThreads || n > p.max_n_video || k < 0 || k > budget || budget > n;
@@ -109,36 +135,33 @@ void select_kernel(const SelectParams p)
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = 24 - 8 * pass;
             if (pass == 0) __syncthreads();             // the cleared histograms are visible
+            // The copies are summed afterwards, so a lane may add to any of them: every lane of an
+            // instruction has a copy of its own (an LDS atomic serialises over the lanes that hit one
+            // address, and the leading digit of attention scores, sign and exponent, takes only a handful
+            // of values), the waves start at different copies, and a copy is 257 words long, so the copies
+            // of a digit lie in different banks.  No aggregation over the wave or over a thread's keys:
+            // both were measured and cost more than the additions they save.
+            int* const my_hist = &s_hist[pass & 1][(4 * wave + lane) & (kSelCopies - 1)][0];
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const bool match = ((valid >> e) & 1) && ((key[e] & known) == prefix);
-                const uint64_t act = __ballot(match);
-                if (act == 0) continue;
-                const int digit = (key[e] >> shift) & 255;
-                const int leader = __ffsll((long long)act) - 1;
-                const int d0 = __builtin_amdgcn_readlane(digit, leader);      // leader is wave-uniform: no LDS crossbar trip
-                const uint64_t same = __ballot(match && digit == d0);
-                if (same == act) {                      // whole wave agrees: one add
-                    if (lane == leader) atomicAdd(&s_hist[pass & 1][wave][d0], __popcll(act));
-                } else if (match) {
-                    // The 16 per-wave histograms are summed afterwards, so a lane may add to any of
-                    // them: lanes of one instruction that share a digit are spread over all 16 copies
-                    // (an LDS atomic serialises over the lanes that hit one address, and the leading
-                    // digit of attention scores, sign and exponent, takes only a handful of values).
-                    // A copy is 257 words long, so the 16 copies of a digit lie in 16 different banks.
-                    atomicAdd(&s_hist[pass & 1][(wave + lane) & (kSelWaves - 1)][digit], 1);
-                }
+                if (match) atomicAdd(&my_hist[(key[e] >> shift) & 255], 1);
             }
             // the other set (read for the last time two barriers ago) is cleared for the next pass
             if (pass < 3)
-                for (int i = tid; i < kSelWaves * 257; i += kSelThreads) (&s_hist[(pass + 1) & 1][0][0])[i] = 0;
+                for (int i = tid; i < kSelCopies * kSelCopyWords; i += kSelThreads) (&s_hist[(pass + 1) & 1][0][0])[i] = 0;
             __syncthreads();
-            if (tid < 256) {
+            {
+                // thread (quarter, digit) sums a quarter of the digit's copies; the four quarters sit in
+                // the lanes of four different waves, so they meet in LDS
+                const int digit = tid & 255, quarter = tid >> 8;
                 int t = 0;
 #pragma unroll
-                for (int w = 0; w < kSelWaves; ++w) t += s_hist[pass & 1][w][tid];
-                s_tot[tid] = t;
+                for (int w = 0; w < kSelCopies / 4; ++w) t += s_hist[pass & 1][quarter * (kSelCopies / 4) + w][digit];
+                s_part[quarter][digit] = t;
             }
+            __syncthreads();
+            if (tid < 256) s_tot[tid] = s_part[0][tid] + s_part[1][tid] + s_part[2][tid] + s_part[3][tid];
             __syncthreads();
             if (wave == 0) {
                 // lane l owns digits 4l..4l+3; suffix sums from the top digit down
@@ -280,13 +303,13 @@ void top_p_kernel(const TopPParams p)
     // a value that is not a finite positive number carries no mass; its key still ranks it
     auto mass_of = [](float x) { return (x > 0.f && x < INFINITY) ? x : 0.f; };
     float val[E];
+    load_run<E>(sc, first, per, n, val);
     uint64_t valid = 0;
     float mx = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int idx = first + e;
         const bool ok = e < per && idx < n;
-        val[e] = ok ? sc[idx] : 0.f;
         if (ok) valid |= 1ull << e;
         mx = fmaxf(mx, mass_of(val[e]));
     }
@@ -398,6 +421,25 @@ void top_p_kernel(const TopPParams p)
     }
 }
 
+// The histogram copies take more LDS than a kernel gets by default: the limit is raised once per
+// device (the attribute belongs to the kernel as loaded on one device).
+template <int E>
+static int launch_select(int batch, const SelectParams& p, hipStream_t stream)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> raised[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECVLM_ELAUNCH;
+    if (!raised[dev].load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<E>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelHistBytes) != hipSuccess)
+            return SPECVLM_ELAUNCH;
+        raised[dev].store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(select_kernel<E>, dim3(batch), dim3(kSelThreads), kSelHistBytes, stream, p);
+    return SPECVLM_OK;
+}
+
 }  // namespace specvlm
 
 using namespace specvlm;
@@ -434,10 +476,12 @@ extern "C" int specvlm_select(
     p.keep_idx = keep_idx; p.from_topk = from_topk; p.status = status;
     hipStream_t s = (hipStream_t)stream;
     const int per = (max_n_video + kSelThreads - 1) / kSelThreads;
-    if (per <= 4)       hipLaunchKernelGGL(select_kernel<4>,  dim3(batch), dim3(kSelThreads), 0, s, p);
-    else if (per <= 16) hipLaunchKernelGGL(select_kernel<16>, dim3(batch), dim3(kSelThreads), 0, s, p);
-    else if (per <= 32) hipLaunchKernelGGL(select_kernel<32>, dim3(batch), dim3(kSelThreads), 0, s, p);
-    else                hipLaunchKernelGGL(select_kernel<64>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    int rc;
+    if (per <= 4)       rc = launch_select<4>(batch, p, s);
+    else if (per <= 16) rc = launch_select<16>(batch, p, s);
+    else if (per <= 32) rc = launch_select<32>(batch, p, s);
+    else                rc = launch_select<64>(batch, p, s);
+    if (rc != SPECVLM_OK) return rc;
     return launch_status();
 }
 
