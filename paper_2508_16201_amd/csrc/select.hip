@@ -94,7 +94,6 @@ void select_kernel(const SelectParams p)
     // kSelCopies copies of the digit histogram (padded: see below); the passes alternate between two sets
     extern __shared__ int s_hist_dyn[];
     int (*s_hist)[kSelCopies][kSelCopyWords] = reinterpret_cast<int (*)[kSelCopies][kSelCopyWords]>(s_hist_dyn);
-    __shared__ int s_tot[256];
     __shared__ int s_part[4][256];
     __shared__ int s_wave2[2][kSelWaves];
     __shared__ int s_pick[2];
@@ -161,13 +160,14 @@ void select_kernel(const SelectParams p)
                 s_part[quarter][digit] = t;
             }
             __syncthreads();
-            if (tid < 256) s_tot[tid] = s_part[0][tid] + s_part[1][tid] + s_part[2][tid] + s_part[3][tid];
-            __syncthreads();
             if (wave == 0) {
                 // lane l owns digits 4l..4l+3; suffix sums from the top digit down
                 int c4[4], mine = 0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { c4[i] = s_tot[4 * lane + i]; mine += c4[i]; }
+                for (int i = 0; i < 4; ++i) {
+                    c4[i] = s_part[0][4 * lane + i] + s_part[1][4 * lane + i] + s_part[2][4 * lane + i] + s_part[3][4 * lane + i];
+                    mine += c4[i];
+                }
                 int incl = mine;                        // inclusive suffix sum over lanes >= lane
 #pragma unroll
                 for (int off = 1; off < 64; off <<= 1) {
