@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--score-lse", action="store_true",
                     help="hand the score call each row's softmax normaliser (as a prefill attention would "
                          "have saved it), so scoring is one sweep per layer")
+    ap.add_argument("--score-per-layer", action="store_true",
+                    help="score with one specvlm_score call per verifier layer (4 launches each) instead of one "
+                         "specvlm_score_layers call for all layers (4 launches in all)")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count (with --attn-only)")
     ap.add_argument("--attn-only", action="store_true",
                     help="time only the verify attention of --workload (32b-long, ragged-x8, ...): extra context "
@@ -191,7 +194,8 @@ def main():
 
     # ---- workspaces and outputs, allocated once ----
     ws_attn_bytes = B.decode_attn_workspace_bytes(1, g1, kv_len, hq, hkv, d, args.num_splits)
-    ws_score = B.new_workspace(B.score_workspace_bytes(T, n_ctx, V, hq, hkv, d), dev)
+    ws_score = B.new_workspace(max(B.score_workspace_bytes(T, n_ctx, V, hq, hkv, d),
+                                   B.score_layers_workspace_bytes(L, T, n_ctx, V, hq, hkv, d)), dev)
     ws_attn = B.new_workspace(ws_attn_bytes, dev)
     ws_dattn = B.new_workspace(B.decode_attn_workspace_bytes(1, 1, n_pruned + g1, dq, dkv, dd, 0), dev)
     ws_acc = B.new_workspace(B.accept_workspace_bytes(1, w.gamma, w.vocab, args.sampling), dev)
@@ -222,6 +226,11 @@ def main():
         del qf, kf, logits
 
     def st_score():
+        if not args.score_per_layer:
+            # every verifier layer in one call: the text queries of all layers are kept until the prefill ends
+            B.score_layers(q_text, k_all[:, :n_ctx], 0, V, V, scale, row_lse=row_lse, scores=scores,
+                           workspace=ws_score)
+            return
         for l in range(L):
             B.score(q_text[l], k_all[l, :n_ctx], 0, V, V, scale, beta=(1.0 if l else 0.0),
                     row_lse=None if row_lse is None else row_lse[l], scores=scores, workspace=ws_score)
@@ -315,6 +324,7 @@ def main():
                    "kv_layout": args.layout, "num_splits": args.num_splits,
                    "accept": "sampling" if args.sampling else "greedy",
                    "score_row_lse": "supplied (torch logsumexp at set-up, untimed)" if args.score_lse else "computed",
+                   "score_call": "one call per layer" if args.score_per_layer else "one call for all layers",
                    "launch": "eager" if args.eager else "hip-graph per stage"},
         "value_source": "verify_attn stage inside the timed steps (mean over steps)",
         "in_step_note": "inside a step the verify stage is the first pass over the 4.2 GB cache after the other stages ran; a "

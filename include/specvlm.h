@@ -114,6 +114,38 @@ int specvlm_score(
     void* workspace, size_t workspace_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * specvlm_score_layers -- the same scores, summed over n_layers layers in one
+ * call (Sec. 3.1: "averaging across all layers and heads"; the sum over layers
+ * is what n_layers calls of specvlm_score with beta = 1 accumulate):
+ *
+ *   scores = beta * scores + sum_l (1/(H_q n_text)) sum_{h,i} G_l
+ *
+ * Layer l reads q_text + l * q_layer_stride and k_cache + l * k_layer_stride
+ * (strides in elements, multiples of 8; 0 is allowed and reads the same tensor
+ * again) and, when row_lse is given, row_lse + l * row_lse_layer_stride floats.
+ * Everything else is as for specvlm_score, including the batch.  One set of four
+ * launches serves all layers (a caller that keeps the text queries of every
+ * layer until the prefill has ended pays for 4 launches instead of 4 n_layers,
+ * and every launch has n_layers times the workgroups to fill the chip with).
+ * n_layers = 0 only applies beta.  n_layers * batch <= 65535.
+ * The workspace query takes n_layers as well; the result is deterministic (the
+ * layers are added in the order 0, 1, ...), and equals what the per-layer calls
+ * give up to the rounding of one fp32 sum taken in a different order.
+ * -------------------------------------------------------------------------- */
+size_t specvlm_score_layers_workspace_bytes(int n_layers, int batch, int n_text, int n_keys, int n_video,
+                                            int n_q_heads, int n_kv_heads, int head_dim,
+                                            int have_row_lse);
+
+int specvlm_score_layers(
+    const void* q_text,  int64_t q_layer_stride, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_layer_stride, int64_t k_tok_stride, int64_t k_head_stride, int n_layers,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, int64_t row_lse_layer_stride, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
  * specvlm_select -- the two-stage retention set  (Sec. 3.2).
  *
  * Stage I: V_R = the k_top highest-scoring video tokens (Eq. 6 sizes V_R by

@@ -22,6 +22,7 @@ _lib = None
 EXPORTS = (
     "specvlm_status_string", "specvlm_version",
     "specvlm_score_workspace_bytes", "specvlm_score",
+    "specvlm_score_layers_workspace_bytes", "specvlm_score_layers",
     "specvlm_select_workspace_bytes", "specvlm_select",
     "specvlm_top_p_count_workspace_bytes", "specvlm_top_p_count",
     "specvlm_gather_kv",
@@ -60,6 +61,10 @@ def lib() -> C.CDLL:
         l.specvlm_score.argtypes = [vp, i64, i64, vp, i64, i64, vp, vp, vp, i32,
                                     i32, i32, i32, i32, i32, i32, i32, i32, f32,
                                     i32, vp, f32, vp, vp, sz, vp]
+        l.specvlm_score_layers_workspace_bytes.argtypes = [i32] * 9
+        l.specvlm_score_layers.argtypes = [vp, i64, i64, i64, vp, i64, i64, i64, i32, vp, vp, vp, i32,
+                                           i32, i32, i32, i32, i32, i32, i32, i32, f32,
+                                           i32, vp, i64, f32, vp, vp, sz, vp]
         l.specvlm_select_workspace_bytes.argtypes = [i32, i32]
         l.specvlm_select.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         l.specvlm_top_p_count_workspace_bytes.argtypes = [i32, i32]
@@ -141,6 +146,42 @@ def score_workspace_bytes(n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_d
                           have_row_lse=False, batch=1) -> int:
     return lib().specvlm_score_workspace_bytes(batch, n_text, n_keys, n_video, n_q_heads, n_kv_heads,
                                                head_dim, int(have_row_lse))
+
+
+def score_layers_workspace_bytes(n_layers, n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_dim,
+                                 have_row_lse=False, batch=1) -> int:
+    return lib().specvlm_score_layers_workspace_bytes(n_layers, batch, n_text, n_keys, n_video, n_q_heads,
+                                                      n_kv_heads, head_dim, int(have_row_lse))
+
+
+def score_layers(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
+                 text_pos0: int, softmax_scale: float, *, norm_mode: int = 0,
+                 row_lse: Optional[torch.Tensor] = None, beta: float = 0.0,
+                 scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q_text [layers,L,H_q,d] bf16, k_cache [layers,n_keys,H_kv,d] bf16 (any layer / token / head strides with
+    contiguous d), row_lse [layers,L,H_q] fp32 or None -> scores fp32 [n_video] summed over the layers."""
+    n_layers, n_text, hq, d = q_text.shape
+    _, n_keys, hkv, _ = k_cache.shape
+    if k_cache.shape[0] != n_layers:
+        raise ValueError("q_text and k_cache must have the same number of layers")
+    if q_text.stride(3) != 1 or k_cache.stride(3) != 1:
+        raise ValueError("the head dimension must be contiguous")
+    if row_lse is not None and (row_lse.shape != (n_layers, n_text, hq) or not row_lse[0].is_contiguous()):
+        raise ValueError("row_lse must be [layers, n_text, H_q] with contiguous layers")
+    if scores is None:
+        scores = torch.empty(n_video, dtype=torch.float32, device=q_text.device)
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs an existing scores tensor")
+    need = score_layers_workspace_bytes(n_layers, n_text, n_keys, n_video, hq, hkv, d, row_lse is not None)
+    workspace = _ws(workspace, need, q_text)
+    rc = lib().specvlm_score_layers(_ptr(q_text), q_text.stride(0), q_text.stride(1), q_text.stride(2),
+                                    _ptr(k_cache), k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), n_layers,
+                                    None, None, None, 1, n_text, n_keys, video_start, n_video, text_pos0, hq, hkv, d,
+                                    float(softmax_scale), norm_mode, _ptr(row_lse),
+                                    0 if row_lse is None else row_lse.stride(0), float(beta), _ptr(scores),
+                                    _ptr(workspace), workspace.numel(), _stream())
+    _check("specvlm_score_layers", rc)
+    return scores
 
 
 def _dev_i32(a, device):

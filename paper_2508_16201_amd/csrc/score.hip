@@ -75,18 +75,26 @@ struct ScoreParams {
     const int32_t* cu_keys;
     const int32_t* cu_video;
     int batch, norm_mode;
-    int64_t ws_ml, ws_lse, ws_cols;    // floats per request in part_ml / lse2 / part_cols
+    int64_t ws_ml, ws_lse, ws_cols;    // floats per (layer, request) in part_ml / lse2 / part_cols
+    // several layers in one call: layer l reads q + l*q_layer, k + l*k_layer, row_lse + l*lse_layer and owns
+    // the workspace slices l*batch .. l*batch + batch - 1; the final kernel sums the layers
+    int n_layers;
+    int64_t q_layer, k_layer, lse_layer;
 };
 
-// Request b's view of the launch parameters: pointers moved to its rows, sizes and positions its
-// own.  The plan (padding, split sizes) stays that of the maxima, so a workgroup whose share lies
-// beyond the request's real size finds an empty range.  Returns false for a request whose sizes do
-// not fit the maxima or each other: every kernel skips it.
-__device__ __forceinline__ bool score_select_request(ScoreParams& p, int b)
+// The view of (layer, request) number idx = layer * batch + b of the launch parameters: pointers moved
+// to its layer and rows, sizes and positions its own.  The plan (padding, split sizes) stays that of
+// the maxima, so a workgroup whose share lies beyond the request's real size finds an empty range.
+// Returns false for a request whose sizes do not fit the maxima or each other: every kernel skips it.
+__device__ __forceinline__ bool score_select_request(ScoreParams& p, int idx)
 {
-    p.part_ml += (int64_t)b * p.ws_ml;
-    p.lse2 += (int64_t)b * p.ws_lse;
-    p.part_cols += (int64_t)b * p.ws_cols;
+    const int layer = idx / p.batch, b = idx - layer * p.batch;
+    p.part_ml += (int64_t)idx * p.ws_ml;
+    p.lse2 += (int64_t)idx * p.ws_lse;
+    p.part_cols += (int64_t)idx * p.ws_cols;
+    p.q += layer * p.q_layer;
+    p.k += layer * p.k_layer;
+    if (p.row_lse) p.row_lse += layer * p.lse_layer;
     if (!p.cu_text) return true;
     const int t0 = p.cu_text[b], k0 = p.cu_keys[b], v0 = p.cu_video[b];
     const int nt = p.cu_text[b + 1] - t0, nk = p.cu_keys[b + 1] - k0, nv = p.cu_video[b + 1] - v0;
@@ -197,7 +205,7 @@ void score_sweep_kernel(const ScoreParams p_launch)
     const int n_blocks = (MODE == 0 ? p.rows_pad : p.video_pad) / kScoreBlock;
     const int n_split = (MODE == 0 ? p.a_splits : p.b_splits);
     const int vid = xcd_logical_id(blockIdx.x, gridDim.x);
-    if (vid >= n_blocks * n_split * p.n_kv_heads * p.batch) return;
+    if (vid >= n_blocks * n_split * p.n_kv_heads * p.batch * p.n_layers) return;
     const int blk = vid % n_blocks;
     const int split = (vid / n_blocks) % n_split;
     const int g = (vid / (n_blocks * n_split)) % p.n_kv_heads;
@@ -503,19 +511,23 @@ __global__ __launch_bounds__(256)
 void score_final_kernel(const ScoreParams p_launch)
 {
     ScoreParams p = p_launch;
-    if (!score_select_request(p, blockIdx.y)) return;
+    if (!score_select_request(p, blockIdx.y)) return;           // (layer 0 of request blockIdx.y)
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= p.n_video) return;
     float a = 0.f;
     const int parts = p.n_kv_heads * p.b_splits;
-    // eight loads in flight at a time; the additions keep the order s = 0, 1, 2, ...
-    for (int s0 = 0; s0 < parts; s0 += 8) {
-        float v[8];
+    // layer after layer, eight loads in flight at a time; the additions keep the order layer 0, 1, ... and
+    // inside a layer s = 0, 1, 2, ...
+    for (int layer = 0; layer < p.n_layers; ++layer) {
+        const float* cols = p.part_cols + (int64_t)layer * p.batch * p.ws_cols;
+        for (int s0 = 0; s0 < parts; s0 += 8) {
+            float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            v[u] = (s0 + u < parts) ? p.part_cols[(int64_t)(s0 + u) * p.video_pad + j] : 0.f;
+            for (int u = 0; u < 8; ++u)
+                v[u] = (s0 + u < parts) ? cols[(int64_t)(s0 + u) * p.video_pad + j] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a += v[u];
+            for (int u = 0; u < 8; ++u) a += v[u];
+        }
     }
     a *= p.inv_count;
     p.scores[j] = (p.beta != 0.f ? p.beta * p.scores[j] : 0.f) + a;
@@ -578,29 +590,40 @@ static ScorePlan score_plan(int batch, int n_text, int n_keys, int video_start, 
 
 using namespace specvlm;
 
+extern "C" size_t specvlm_score_layers_workspace_bytes(int n_layers, int batch, int n_text, int n_keys, int n_video,
+                                                       int n_q_heads, int n_kv_heads, int head_dim,
+                                                       int have_row_lse)
+{
+    if (n_layers < 1 || batch < 1 || (int64_t)n_layers * batch > 65535 || n_text < 0 || n_keys < 0 || n_video < 0 ||
+        n_video > n_keys || n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
+        return 0;
+    // every (layer, request) has its own slice, sized by the plan of the maxima; the split plan
+    // depends on the normalisation domain: size for the larger one
+    const int units = n_layers * batch;
+    const ScorePlan a = score_plan(units, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
+    const ScorePlan b = score_plan(units, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
+    return (size_t)units * (a.total > b.total ? a.total : b.total);
+}
+
 extern "C" size_t specvlm_score_workspace_bytes(int batch, int n_text, int n_keys, int n_video,
                                                 int n_q_heads, int n_kv_heads, int head_dim,
                                                 int have_row_lse)
 {
-    if (batch < 1 || n_text < 0 || n_keys < 0 || n_video < 0 || n_video > n_keys ||
-        n_kv_heads <= 0 || n_q_heads <= 0 || n_q_heads % n_kv_heads)
-        return 0;
-    // every request of a batch has its own slice, sized by the plan of the maxima; the split plan
-    // depends on the normalisation domain: size for the larger one
-    const ScorePlan a = score_plan(batch, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 0, have_row_lse);
-    const ScorePlan b = score_plan(batch, n_text, n_keys, 0, n_video, n_q_heads, n_kv_heads, head_dim, 1, have_row_lse);
-    return (size_t)batch * (a.total > b.total ? a.total : b.total);
+    return specvlm_score_layers_workspace_bytes(1, batch, n_text, n_keys, n_video, n_q_heads, n_kv_heads, head_dim,
+                                                have_row_lse);
 }
 
-extern "C" int specvlm_score(
-    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
-    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
+static int score_impl(
+    const void* q_text,  int64_t q_layer_stride, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_layer_stride, int64_t k_tok_stride, int64_t k_head_stride, int n_layers,
     const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
     int n_text, int n_keys, int video_start, int n_video, int text_pos0,
     int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
-    int norm_mode, const float* row_lse, float beta, float* scores,
+    int norm_mode, const float* row_lse, int64_t lse_layer_stride, float beta, float* scores,
     void* workspace, size_t workspace_bytes, void* stream)
 {
+    if (n_layers < 0) return SPECVLM_EINVAL;
+    if ((q_layer_stride | k_layer_stride) & 7) return SPECVLM_EUNSUPPORTED;
     if (batch < 0 || text_pos0 < -1) return SPECVLM_EINVAL;
     if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads) return SPECVLM_EINVAL;
     if (norm_mode != 0 && norm_mode != 1) return SPECVLM_EINVAL;
@@ -614,7 +637,7 @@ extern "C" int specvlm_score(
     const bool ragged = cu_text || cu_keys || cu_video;
     if (ragged && !(cu_text && cu_keys && cu_video)) return SPECVLM_EINVAL;
     if (!ragged && batch != 1) return SPECVLM_EINVAL;
-    if (batch > 65535) return SPECVLM_EUNSUPPORTED;
+    if ((int64_t)batch * (n_layers > 0 ? n_layers : 1) > 65535) return SPECVLM_EUNSUPPORTED;
     if (n_text < 0 || n_keys < 0 || video_start < 0 || n_video < 0) return SPECVLM_EINVAL;
     if ((int64_t)video_start + n_video > n_keys) return SPECVLM_EINVAL;
     if (!ragged) {
@@ -623,14 +646,16 @@ extern "C" int specvlm_score(
     }
     if (n_video == 0) return SPECVLM_OK;
     if (!scores) return SPECVLM_EINVAL;
-    if (n_text > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
+    if (n_text > 0 && n_layers > 0 && (!q_text || !k_cache)) return SPECVLM_EINVAL;
     if (((uintptr_t)q_text | (uintptr_t)k_cache) & 15) return SPECVLM_EUNSUPPORTED;
 
-    // One plan for the whole batch, made from the maxima (the host does not know the requests' own
-    // sizes); a request's kernels find their real sizes in the cu arrays on the device.
-    const ScorePlan plan = score_plan(batch, n_text, n_keys, video_start, n_video, n_q_heads, n_kv_heads,
-                                      head_dim, norm_mode, row_lse != nullptr);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (size_t)batch * plan.total)
+    // One plan for all layers and the whole batch, made from the maxima (the host does not know the
+    // requests' own sizes); a request's kernels find their real sizes in the cu arrays on the device.
+    // Without layers only beta applies (the sum over layers is empty).
+    const int units = batch * n_layers;                 // (layer, request) pairs: one workspace slice each
+    const ScorePlan plan = score_plan(units > 0 ? units : 1, n_text, n_keys, video_start, n_video, n_q_heads,
+                                      n_kv_heads, head_dim, norm_mode, row_lse != nullptr);
+    if (units > 0 && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (size_t)units * plan.total))
         return SPECVLM_EWORKSPACE;
     ScoreParams p;
     p.q = (const __bf16*)q_text; p.k = (const __bf16*)k_cache;
@@ -645,13 +670,13 @@ extern "C" int specvlm_score(
     p.a_splits = plan.a_splits; p.a_split_keys = plan.a_split_keys;
     p.b_splits = plan.b_splits; p.b_split_rows = plan.b_split_rows;
     p.b_needs_mask = (video_start + n_video - 1 > text_pos0) ? 1 : 0;
-    // workspace: [batch] slices of each of the three arrays
+    // workspace: [layers x batch] slices of each of the three arrays
     const size_t n_ml = row_lse ? 0 : (size_t)n_kv_heads * plan.rows_pad * plan.a_splits * 2;
     const size_t n_lse = (size_t)n_kv_heads * plan.rows_pad;
     const size_t n_cols = (size_t)n_kv_heads * plan.b_splits * plan.video_pad;
     char* ws = (char*)workspace;
-    p.part_ml = (float*)ws;  ws += align256(batch * n_ml * sizeof(float));
-    p.lse2 = (float*)ws;     ws += align256(batch * n_lse * sizeof(float));
+    p.part_ml = (float*)ws;  ws += align256(units * n_ml * sizeof(float));
+    p.lse2 = (float*)ws;     ws += align256(units * n_lse * sizeof(float));
     p.part_cols = (float*)ws;
     p.ws_ml = (int64_t)n_ml; p.ws_lse = (int64_t)n_lse; p.ws_cols = (int64_t)n_cols;
     p.row_lse = row_lse;
@@ -660,16 +685,20 @@ extern "C" int specvlm_score(
     p.scores = scores;
     p.cu_text = cu_text; p.cu_keys = cu_keys; p.cu_video = cu_video;
     p.batch = batch; p.norm_mode = norm_mode;
+    p.n_layers = n_layers; p.q_layer = q_layer_stride; p.k_layer = k_layer_stride; p.lse_layer = lse_layer_stride;
     hipStream_t s = (hipStream_t)stream;
 
-    if (n_text > 0) {
+    if (n_text > 0 && n_layers > 0) {
+        if ((int64_t)(plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits * units > 0x7fffff00ll ||
+            (int64_t)(plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits * units > 0x7fffff00ll)
+            return SPECVLM_EUNSUPPORTED;
         if (!row_lse && p.key_hi > p.key_lo) {
-            dim3 grid(round_up((plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits * batch, kNumXcd));
+            dim3 grid(round_up((plan.rows_pad / kScoreBlock) * n_kv_heads * plan.a_splits * units, kNumXcd));
             if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 0>), grid, dim3(256), 0, s, p);
             else                 hipLaunchKernelGGL((score_sweep_kernel<64, 0>), grid, dim3(256), 0, s, p);
         }
-        hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads, batch), dim3(256), 0, s, p);
-        dim3 grid(round_up((plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits * batch, kNumXcd));
+        hipLaunchKernelGGL(score_lse_kernel, dim3(plan.rows_pad / 256, n_kv_heads, units), dim3(256), 0, s, p);
+        dim3 grid(round_up((plan.video_pad / kScoreBlock) * n_kv_heads * plan.b_splits * units, kNumXcd));
         if (head_dim == 128) hipLaunchKernelGGL((score_sweep_kernel<128, 1>), grid, dim3(256), 0, s, p);
         else                 hipLaunchKernelGGL((score_sweep_kernel<64, 1>), grid, dim3(256), 0, s, p);
     } else {
@@ -677,4 +706,34 @@ extern "C" int specvlm_score(
     }
     hipLaunchKernelGGL(score_final_kernel, dim3((n_video + 255) / 256, batch), dim3(256), 0, s, p);
     return launch_status();
+}
+
+extern "C" int specvlm_score(
+    const void* q_text,  int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return score_impl(q_text, 0, q_tok_stride, q_head_stride, k_cache, 0, k_tok_stride, k_head_stride, 1,
+                      cu_text, cu_keys, cu_video, batch, n_text, n_keys, video_start, n_video, text_pos0,
+                      n_q_heads, n_kv_heads, head_dim, softmax_scale, norm_mode, row_lse, 0, beta, scores,
+                      workspace, workspace_bytes, stream);
+}
+
+extern "C" int specvlm_score_layers(
+    const void* q_text,  int64_t q_layer_stride, int64_t q_tok_stride, int64_t q_head_stride,
+    const void* k_cache, int64_t k_layer_stride, int64_t k_tok_stride, int64_t k_head_stride, int n_layers,
+    const int32_t* cu_text, const int32_t* cu_keys, const int32_t* cu_video, int batch,
+    int n_text, int n_keys, int video_start, int n_video, int text_pos0,
+    int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale,
+    int norm_mode, const float* row_lse, int64_t row_lse_layer_stride, float beta, float* scores,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return score_impl(q_text, q_layer_stride, q_tok_stride, q_head_stride, k_cache, k_layer_stride, k_tok_stride,
+                      k_head_stride, n_layers, cu_text, cu_keys, cu_video, batch, n_text, n_keys, video_start,
+                      n_video, text_pos0, n_q_heads, n_kv_heads, head_dim, softmax_scale, norm_mode, row_lse,
+                      row_lse_layer_stride, beta, scores, workspace, workspace_bytes, stream);
 }

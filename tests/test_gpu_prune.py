@@ -61,6 +61,56 @@ def test_score_matches_oracle(B, V, L, P, hq, hkv, d, mode):
     assert_scores_close(got2, want, f"V{V} L{L} mode{mode} row_lse")
 
 
+@pytest.mark.parametrize("n_layers,V,L,P,hq,hkv,d,mode", [
+    (3, 700, 37, 5, 16, 2, 128, 0),
+    (3, 700, 37, 5, 16, 2, 128, 1),
+    (5, 1568, 64, 0, 4, 1, 64, 0),
+    (2, 1176, 70, 0, 28, 4, 128, 0),
+    (1, 600, 20, 0, 8, 2, 128, 0),
+])
+def test_score_layers_is_the_sum_over_layers(B, n_layers, V, L, P, hq, hkv, d, mode):
+    """specvlm_score_layers: one call for all layers = the sum of the oracle's per-layer scores
+    (plus beta times what was there), with and without caller-supplied row normalisers, with layers
+    that are not contiguous in memory, and equal to the per-layer calls accumulated with beta = 1."""
+    n_keys = P + V + L
+    scale = 1 / np.sqrt(d)
+    qs = [rnd_bits((L, hq, d), 900 + 7 * l + V) for l in range(n_layers)]
+    ks = [rnd_bits((n_keys, hkv, d), 950 + 7 * l + V) for l in range(n_layers)]
+    per_layer = [oracle.score(q, k, P, V, P + V, scale, norm_mode=mode, want_lse=True) for q, k in zip(qs, ks)]
+    want = np.sum([w for w, _ in per_layer], axis=0)
+    qd = torch.stack([dev_bf16(q) for q in qs])
+    # the key cache of a layer is a slice of a larger buffer (more tokens allocated than used)
+    k_big = torch.zeros((n_layers, n_keys + 9, hkv, d), dtype=torch.bfloat16, device="cuda")
+    for l, k in enumerate(ks):
+        k_big[l, :n_keys] = dev_bf16(k)
+    kd = k_big[:, :n_keys]
+    got = B.score_layers(qd, kd, P, V, P + V, scale, norm_mode=mode)
+    torch.cuda.synchronize()
+    assert_scores_close(got, want, f"layers{n_layers} V{V} mode{mode}")
+    # caller-supplied row normalisers, and beta on top of earlier contents
+    lse = torch.tensor(np.stack([l for _, l in per_layer]), dtype=torch.float32).cuda()
+    before = torch.full((V,), 0.25 / V, dtype=torch.float32, device="cuda")
+    got2 = B.score_layers(qd, kd, P, V, P + V, scale, norm_mode=mode, row_lse=lse, beta=2.0, scores=before.clone())
+    torch.cuda.synchronize()
+    assert_scores_close(got2, want + 2.0 * 0.25 / V, f"layers{n_layers} V{V} mode{mode} row_lse beta")
+    # the per-layer entry point, accumulated by beta = 1, gives the same numbers up to fp32 summation order
+    acc = torch.zeros(V, dtype=torch.float32, device="cuda")
+    for l in range(n_layers):
+        B.score(qd[l], kd[l], P, V, P + V, scale, norm_mode=mode, beta=1.0 if l else 0.0, scores=acc)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(host_f64(got), host_f64(acc), rtol=2e-6, atol=1e-10)
+
+
+def test_score_layers_without_layers_only_applies_beta(B):
+    V, L, hq, hkv, d = 300, 10, 4, 1, 64
+    q = torch.zeros((0, L, hq, d), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((0, V + L, hkv, d), dtype=torch.bfloat16, device="cuda")
+    s = torch.full((V,), 3.0, dtype=torch.float32, device="cuda")
+    B.score_layers(q, k, 0, V, V, 0.1, beta=0.5, scores=s)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_f64(s), np.full(V, 1.5))
+
+
 def test_score_zero_scale_is_the_closed_form(B):
     """softmax_scale = 0 makes every visible logit 0: mode 1 gives 1/V per token, mode 0 gives
     mean_i 1/(p_i + 1) (the closed forms that pin the oracle), also where causal masks apply."""
