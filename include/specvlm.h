@@ -115,8 +115,9 @@ int specvlm_score(
 
 /* --------------------------------------------------------------------------
  * specvlm_score_layers -- the same scores, summed over n_layers layers in one
- * call (Sec. 3.1: "averaging across all layers and heads"; the sum over layers
- * is what n_layers calls of specvlm_score with beta = 1 accumulate):
+ * call (Sec. 3.1 takes the importance as a mean over the verifier's layers as
+ * well as its heads; the sum over layers is what n_layers calls of
+ * specvlm_score with beta = 1 accumulate):
  *
  *   scores = beta * scores + sum_l (1/(H_q n_text)) sum_{h,i} G_l
  *

@@ -176,8 +176,9 @@ __device__ __forceinline__ void score_rows_max(floatx4 (&acc)[4], bool mask, int
     }
 }
 
+// (register budget: three waves per SIMD, i.e. at most 168 VGPRs, which head size 128 needs all of)
 template <int D, int MODE>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void score_sweep_kernel(const ScoreParams p_launch)
 {
     ScoreParams p = p_launch;
@@ -288,18 +289,26 @@ void score_sweep_kernel(const ScoreParams p_launch)
         if (idx0 + kScoreTile <= limit) {
             const char* tile_base = reinterpret_cast<const char*>(base + (int64_t)idx0 * s_tok + head_off);
 #pragma unroll
-            for (int j = 0; j < LPW; ++j)
-                __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(tile_base + voff[j]),
+            for (int j = 0; j < LPW; ++j) {
+                // (the offset is made opaque here so that it stays one 32-bit register beside a scalar
+                // base: seen through, it is widened to a 64-bit pair outside the loop)
+                uint32_t off = voff[j];
+                asm volatile("" : "+v"(off));
+                __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)(tile_base + off),
                     (SPECVLM_AS3 void*)(s_tile + stage * TILE_BYTES + (wave + 4 * j) * 1024), 16, 0, 0);
+            }
         } else {
             // vectors past the end are masked later (pass A) or carry lse = +inf (pass B): re-read the last one
+            // (rare path: its lane constants are recomputed here instead of living in registers)
+            int lv = ld_vec, lc = ld_chunk;
+            asm volatile("" : "+v"(lv), "+v"(lc));
 #pragma unroll
             for (int j = 0; j < LPW; ++j) {
                 const int n = wave + 4 * j;
-                const int it = n * VEC_PER_LOAD + ld_vec;
+                const int it = n * VEC_PER_LOAD + lv;
                 const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
                 const int idx = min(idx0 + it, limit - 1);
-                const __bf16* src = base + (int64_t)idx * s_tok + head_off + (ld_chunk ^ swz) * 8;
+                const __bf16* src = base + (int64_t)idx * s_tok + head_off + (lc ^ swz) * 8;
                 __builtin_amdgcn_global_load_lds((const SPECVLM_AS1 void*)src,
                     (SPECVLM_AS3 void*)(s_tile + stage * TILE_BYTES + n * 1024), 16, 0, 0);
             }
@@ -316,14 +325,17 @@ void score_sweep_kernel(const ScoreParams p_launch)
     // ---- one tile: 4 sub-blocks of 16 streamed vectors against the wave's 64 stationary ones ----
     // Software pipeline inside the wave: while the VALU turns the logits of sub-block s into
     // exponentials, the matrix unit already forms the logits of sub-block s+1 (independent MFMA and
-    // VALU instructions of one wave overlap), and the A fragments are read from LDS two sub-blocks
-    // ahead.  The order is written out piece by piece -- one MFMA, one logit's fma / exp / add --
-    // and pinned with scheduling barriers: left alone, the scheduler moves every chain of MFMAs
-    // next to its consumer again.  Even sub-blocks live in (af0, acc0), odd ones in (af1, acc1).
+    // VALU instructions of one wave overlap).  The order is written out piece by piece -- one MFMA,
+    // one logit's fma / exp / add -- and pinned with scheduling barriers: left alone, the scheduler
+    // moves every chain of MFMAs next to its consumer again.  Even sub-blocks accumulate in acc0, odd
+    // ones in acc1.  There is ONE set of A fragments: fragment kk of sub-block s+2 is read from LDS
+    // right after the last MFMA of sub-block s+1 that uses fragment kk, most of a sub-block before
+    // its own first use.  (A second set, read a whole sub-block earlier, cost 16 registers and with
+    // them the third wave per SIMD at head size 128.)
     // (a zero scale is taken as a vanishing one, so that a masked logit, -inf, times the scale stays
     // -inf instead of becoming NaN; every other logit still scales to 0)
     const float sc_a = fmaxf(p.scale_log2, 1e-30f);
-    auto step = [&](floatx4 (&acc_cur)[4], floatx4 (&acc_nxt)[4], bf16x8 (&af_cur)[KK], const bf16x8 (&af_nxt)[KK],
+    auto step = [&](floatx4 (&acc_cur)[4], floatx4 (&acc_nxt)[4], bf16x8 (&af)[KK],
                     const unsigned char* tile, const unsigned char* lse_w, const int sub, const int first,
                     const int lim0, const bool mask, const bool track, const bool has_next, const bool has_load)
         __attribute__((always_inline)) {
@@ -341,13 +353,15 @@ void score_sweep_kernel(const ScoreParams p_launch)
             if (has_next && i < 4 * KK) {
                 // neighbours in this order are independent: the four accumulators take turns
                 const int kk = i / 4, sb = i % 4;
-                acc_nxt[sb] = mfma16(af_nxt[kk], sf[sb][kk], kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc_nxt[sb]);
+                acc_nxt[sb] = mfma16(af[kk], sf[sb][kk], kk == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc_nxt[sb]);
             }
-            if (has_load && i < KK) {
+            if (has_load && i >= 4 && i % 4 == 0 && i / 4 - 1 < KK) {
+                // fragment kk of the sub-block after the next one, right after its last reader
+                const int kk = i / 4 - 1;
                 const int it = (sub + 2) * 16 + r;
                 const int swz = (D == 128) ? (it & 15) : ((it >> 1) & 7);
-                af_cur[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                    tile + it * ROW_BYTES + (((i * 4 + c) ^ swz) * 16)));
+                af[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                    tile + it * ROW_BYTES + (((kk * 4 + c) ^ swz) * 16)));
             }
             if (i >= 2) {                                   // add logit i-2
                 const int sb = (i - 2) / 4, e = (i - 2) % 4;
@@ -376,15 +390,15 @@ void score_sweep_kernel(const ScoreParams p_launch)
         const unsigned char* tile = s_tile + stage * TILE_BYTES;
         const unsigned char* lse_w = s_lse + (stage * 4 + wave) * LSE_BYTES;
         const int lim0 = (MODE == 1) ? p.text_pos0 + i0 + 4 * c : 0;      // i0: the tile's first text query
-        bf16x8 af0[KK], af1[KK];
+        bf16x8 af[KK];
         floatx4 acc0[4], acc1[4];
-        score_load_a<D>(tile, 0, r, c, af0);
-        score_load_a<D>(tile, 1, r, c, af1);
-        score_mfma<KK>(af0, sf, acc0);
-        step(acc0, acc1, af0, af1, tile, lse_w, 0, first, lim0, mask, track, true, true);
-        step(acc1, acc0, af1, af0, tile, lse_w, 1, first, lim0, mask, track, true, true);
-        step(acc0, acc1, af0, af1, tile, lse_w, 2, first, lim0, mask, track, true, false);
-        step(acc1, acc0, af1, af0, tile, lse_w, 3, first, lim0, mask, track, false, false);
+        score_load_a<D>(tile, 0, r, c, af);
+        score_mfma<KK>(af, sf, acc0);
+        score_load_a<D>(tile, 1, r, c, af);
+        step(acc0, acc1, af, tile, lse_w, 0, first, lim0, mask, track, true, true);
+        step(acc1, acc0, af, tile, lse_w, 1, first, lim0, mask, track, true, true);
+        step(acc0, acc1, af, tile, lse_w, 2, first, lim0, mask, track, true, false);
+        step(acc1, acc0, af, tile, lse_w, 3, first, lim0, mask, track, false, false);
     };
     auto compute = [&](int stage, int first, int i0, bool first_tile) __attribute__((always_inline)) {
         // the mask is uniform over the tile (pass A) or the launch (pass B): copies of the
@@ -402,16 +416,16 @@ void score_sweep_kernel(const ScoreParams p_launch)
         // against the reference the earlier tiles left; a logit far above it only makes the sum
         // large, and a sum that is no longer a moderate finite number (overflow, or the
         // reference still unset) sends the wave back over the same tile with tracking on.
-        float l_save[4], m_save[4];
+        float l_save[4];                      // (the references do not move without tracking)
 #pragma unroll
-        for (int sb = 0; sb < 4; ++sb) { l_save[sb] = l_run[sb]; m_save[sb] = m_ref[sb]; }
+        for (int sb = 0; sb < 4; ++sb) l_save[sb] = l_run[sb];
         tile_body(stage, first, i0, false, false);
         bool redo = false;
 #pragma unroll
         for (int sb = 0; sb < 4; ++sb) redo = redo || !(l_run[sb] < kSumRedo);
         if (__any(redo)) {
 #pragma unroll
-            for (int sb = 0; sb < 4; ++sb) { l_run[sb] = l_save[sb]; m_ref[sb] = m_save[sb]; }
+            for (int sb = 0; sb < 4; ++sb) l_run[sb] = l_save[sb];
             tile_body(stage, first, i0, false, true);
         }
     };
@@ -549,13 +563,13 @@ static ScorePlan score_plan(int batch, int n_text, int n_keys, int video_start, 
     s.video_pad = round_up(n_video > 0 ? n_video : 1, kScoreBlock);
     s.key_lo = norm_mode ? video_start : 0;
     s.key_hi = norm_mode ? video_start + n_video : n_keys;
-    // Workgroups resident per CU: two at head size 128 (about 190 VGPRs with the software
-    // pipeline's second set of fragments and accumulators), three at 64.  The dispatcher hands a
+    // Workgroups resident per CU: three at head size 128 (168 VGPRs, 51 KB of LDS each), four at
+    // 64.  The dispatcher hands a
     // CU its next workgroup as soon as one ends, so a CU that is dealt w workgroups works through
     // them `resident` at a time: its time is about max(w, resident) / resident workgroup
     // lifetimes (below `resident` the CU is under-used, not faster).  Minimise that, ties to the
     // fewer splits (less partial traffic).
-    const int resident = head_dim == 128 ? 2 : 3;
+    const int resident = head_dim == 128 ? 3 : 4;
     auto best_splits = [&](int blocks, int streamed, int max_splits, int* per_split) {
         int best = 1, best_per = round_up(streamed > 0 ? streamed : 1, kScoreTile);
         long best_cost = -1;

@@ -42,6 +42,9 @@ def test_workspace_queries_are_pure_host_functions(B):
     assert B.decode_attn_workspace_bytes(1, 9, 12806, 64, 8, 128) > 0       # 72 rows per kv head: two row groups
     assert B.decode_attn_workspace_bytes(1, 65, 12806, 64, 8, 128) == 0     # more than 64 queries per request
     assert B.score_workspace_bytes(256, 12800, 12544, 64, 8, 128) > 0
+    per_layer = B.score_workspace_bytes(256, 12800, 12544, 64, 8, 128)
+    assert B.score_layers_workspace_bytes(1, 256, 12800, 12544, 64, 8, 128) == per_layer
+    assert B.score_layers_workspace_bytes(80, 256, 12800, 12544, 64, 8, 128) > per_layer
     assert B.accept_workspace_bytes(1, 5, 152064, True) >= B.accept_workspace_bytes(1, 5, 152064, False) > 0
     assert B.lib().specvlm_select_workspace_bytes(8, 32768) == 0
 
@@ -66,6 +69,16 @@ def test_bad_arguments_are_rejected_before_any_launch(B):
     rc = lib.specvlm_score(null, 0, 0, null, 0, 0, null, null, null, 1, 4, 10, 8, 4, 12, 4, 2, 128, 0.1,
                            0, null, 0.0, null, null, 0, null)
     assert rc == -1
+    # score_layers: the same checks, plus the layer count and the layer strides
+    rc = lib.specvlm_score_layers(null, 0, 0, 0, null, 0, 0, 0, 2, null, null, null, 1, 4, 10, 8, 4, 12, 4, 2, 128,
+                                  0.1, 0, null, 0, 0.0, null, null, 0, null)
+    assert rc == -1
+    rc = lib.specvlm_score_layers(null, 0, 0, 0, null, 0, 0, 0, -1, null, null, null, 1, 4, 10, 0, 4, 6, 4, 2, 128,
+                                  0.1, 0, null, 0, 0.0, null, null, 0, null)
+    assert rc == -1
+    rc = lib.specvlm_score_layers(null, 4, 0, 0, null, 0, 0, 0, 2, null, null, null, 1, 4, 10, 0, 4, 6, 4, 2, 128,
+                                  0.1, 0, null, 0, 0.0, null, null, 0, null)
+    assert rc == -2                                                          # layer stride not a multiple of 8
     rc = lib.specvlm_gather_kv(null, null, 0, 0, 0, null, null, 0, 0, 0, 1, 10, 0, 4, null, 5,
                                null, null, null, 1, null, 2, 128, null)
     assert rc == -1
