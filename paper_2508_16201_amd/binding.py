@@ -154,12 +154,45 @@ def score_layers_workspace_bytes(n_layers, n_text, n_keys, n_video, n_q_heads, n
                                                       n_kv_heads, head_dim, int(have_row_lse))
 
 
+def _dev_i32(a, device):
+    """Device int32 prefix offsets; a host sequence is uploaded (and its maxima returned)."""
+    if isinstance(a, torch.Tensor):
+        return a, None
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+    return torch.from_numpy(arr).to(device), arr
+
+
+def _batch_sizes(device, cu_text, cu_keys, cu_video, n_text, n_keys, n_video, max_n_text, max_n_keys,
+                 max_n_video, total_video):
+    """(batch, device offset arrays, maxima, total video tokens) of a score call; one request without offsets."""
+    if cu_text is None:
+        return 1, (None, None, None), n_text, n_keys, n_video, n_video
+    dev = [_dev_i32(a, device) for a in (cu_text, cu_keys, cu_video)]
+    ptrs = tuple(x[0] for x in dev)
+    batch = ptrs[0].numel() - 1
+    hosts = [x[1] for x in dev]
+    if all(h is not None for h in hosts):
+        n_text = int(np.diff(hosts[0]).max()) if batch else 0
+        n_keys = int(np.diff(hosts[1]).max()) if batch else 0
+        n_video = int(np.diff(hosts[2]).max()) if batch else 0
+        total_video = int(hosts[2][-1])
+    else:
+        if None in (max_n_text, max_n_keys, max_n_video, total_video):
+            raise ValueError("device cu arrays need max_n_text, max_n_keys, max_n_video and total_video")
+        n_text, n_keys, n_video = max_n_text, max_n_keys, max_n_video
+    return batch, ptrs, n_text, n_keys, n_video, total_video
+
+
 def score_layers(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
                  text_pos0: int, softmax_scale: float, *, norm_mode: int = 0,
                  row_lse: Optional[torch.Tensor] = None, beta: float = 0.0,
-                 scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 cu_text=None, cu_keys=None, cu_video=None, max_n_text: Optional[int] = None,
+                 max_n_keys: Optional[int] = None, max_n_video: Optional[int] = None,
+                 total_video: Optional[int] = None) -> torch.Tensor:
     """q_text [layers,L,H_q,d] bf16, k_cache [layers,n_keys,H_kv,d] bf16 (any layer / token / head strides with
-    contiguous d), row_lse [layers,L,H_q] fp32 or None -> scores fp32 [n_video] summed over the layers."""
+    contiguous d), row_lse [layers,L,H_q] fp32 or None -> scores fp32 [n_video] summed over the layers.
+    A batch is given as for score(): requests concatenated along the token axis of every layer."""
     n_layers, n_text, hq, d = q_text.shape
     _, n_keys, hkv, _ = k_cache.shape
     if k_cache.shape[0] != n_layers:
@@ -168,28 +201,25 @@ def score_layers(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, 
         raise ValueError("the head dimension must be contiguous")
     if row_lse is not None and (row_lse.shape != (n_layers, n_text, hq) or not row_lse[0].is_contiguous()):
         raise ValueError("row_lse must be [layers, n_text, H_q] with contiguous layers")
+    batch, ptrs, n_text, n_keys, n_video, total_video = _batch_sizes(
+        q_text.device, cu_text, cu_keys, cu_video, n_text, n_keys, n_video, max_n_text, max_n_keys, max_n_video,
+        total_video)
     if scores is None:
-        scores = torch.empty(n_video, dtype=torch.float32, device=q_text.device)
+        scores = torch.empty(total_video, dtype=torch.float32, device=q_text.device)
         if beta != 0.0:
             raise ValueError("beta != 0 needs an existing scores tensor")
-    need = score_layers_workspace_bytes(n_layers, n_text, n_keys, n_video, hq, hkv, d, row_lse is not None)
+    need = score_layers_workspace_bytes(n_layers, n_text, n_keys, n_video, hq, hkv, d, row_lse is not None,
+                                        batch=max(batch, 1))
     workspace = _ws(workspace, need, q_text)
     rc = lib().specvlm_score_layers(_ptr(q_text), q_text.stride(0), q_text.stride(1), q_text.stride(2),
                                     _ptr(k_cache), k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), n_layers,
-                                    None, None, None, 1, n_text, n_keys, video_start, n_video, text_pos0, hq, hkv, d,
+                                    _ptr(ptrs[0]), _ptr(ptrs[1]), _ptr(ptrs[2]), batch, n_text, n_keys, video_start,
+                                    n_video, text_pos0, hq, hkv, d,
                                     float(softmax_scale), norm_mode, _ptr(row_lse),
                                     0 if row_lse is None else row_lse.stride(0), float(beta), _ptr(scores),
                                     _ptr(workspace), workspace.numel(), _stream())
     _check("specvlm_score_layers", rc)
     return scores
-
-
-def _dev_i32(a, device):
-    """Device int32 prefix offsets; a host sequence is uploaded (and its maxima returned)."""
-    if isinstance(a, torch.Tensor):
-        return a, None
-    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
-    return torch.from_numpy(arr).to(device), arr
 
 
 def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video: int,
@@ -207,23 +237,9 @@ def score(q_text: torch.Tensor, k_cache: torch.Tensor, video_start: int, n_video
     maxima over the batch and the total number of video tokens must be given."""
     n_text, hq, d = q_text.shape
     n_keys, hkv, _ = k_cache.shape
-    batch, ptrs = 1, (None, None, None)
-    if cu_text is not None:
-        dev = [_dev_i32(a, q_text.device) for a in (cu_text, cu_keys, cu_video)]
-        ptrs = tuple(x[0] for x in dev)
-        batch = ptrs[0].numel() - 1
-        hosts = [x[1] for x in dev]
-        if all(h is not None for h in hosts):
-            n_text = int(np.diff(hosts[0]).max()) if batch else 0
-            n_keys = int(np.diff(hosts[1]).max()) if batch else 0
-            n_video = int(np.diff(hosts[2]).max()) if batch else 0
-            total_video = int(hosts[2][-1])
-        else:
-            if None in (max_n_text, max_n_keys, max_n_video, total_video):
-                raise ValueError("device cu arrays need max_n_text, max_n_keys, max_n_video and total_video")
-            n_text, n_keys, n_video = max_n_text, max_n_keys, max_n_video
-    else:
-        total_video = n_video
+    batch, ptrs, n_text, n_keys, n_video, total_video = _batch_sizes(
+        q_text.device, cu_text, cu_keys, cu_video, n_text, n_keys, n_video, max_n_text, max_n_keys, max_n_video,
+        total_video)
     if scores is None:
         scores = torch.empty(total_video, dtype=torch.float32, device=q_text.device)
         if beta != 0.0:

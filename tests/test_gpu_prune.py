@@ -251,6 +251,74 @@ def test_score_ragged_batch_with_row_lse_prefix_and_empty_requests(B):
             assert_scores_close(got2[sl], wants[i], f"request {i} row_lse")
 
 
+def test_score_layers_ragged_batch_equals_the_oracle_sum(B):
+    """Two layers x three requests in one specvlm_score_layers call (device prefix offsets, layer strides):
+    every request's scores are the sum over the layers of the oracle's scores for that request alone,
+    with and without caller-supplied row normalisers."""
+    hq, hkv, d, n_layers = 8, 2, 128, 2
+    Vs, Ls = [600, 196, 900], [33, 70, 9]
+    cu_text = np.concatenate([[0], np.cumsum(Ls)])
+    cu_keys = np.concatenate([[0], np.cumsum([V + L for V, L in zip(Vs, Ls)])])
+    cu_video = np.concatenate([[0], np.cumsum(Vs)])
+    scale = 1.0 / np.sqrt(d)
+    qs = [[rnd_bits((L, hq, d), 400 + 10 * l + i) for i, L in enumerate(Ls)] for l in range(n_layers)]
+    ks = [[rnd_bits((V + L, hkv, d), 450 + 10 * l + i) for i, (V, L) in enumerate(zip(Vs, Ls))]
+          for l in range(n_layers)]
+    qd = torch.stack([dev_bf16(np.concatenate(q)) for q in qs])
+    kd = torch.stack([dev_bf16(np.concatenate(k)) for k in ks])
+    for mode in (0, 1):
+        per = [[oracle.score(qs[l][i], ks[l][i], 0, Vs[i], Vs[i], scale, norm_mode=mode, want_lse=True)
+                for i in range(len(Vs))] for l in range(n_layers)]
+        got = B.score_layers(qd, kd, 0, 0, -1, scale, norm_mode=mode, cu_text=cu_text, cu_keys=cu_keys,
+                             cu_video=cu_video)
+        lse = torch.tensor(np.stack([np.concatenate([per[l][i][1] for i in range(len(Vs))])
+                                     for l in range(n_layers)]), dtype=torch.float32).cuda()
+        got2 = B.score_layers(qd, kd, 0, 0, -1, scale, norm_mode=mode, row_lse=lse, cu_text=i32(cu_text),
+                              cu_keys=i32(cu_keys), cu_video=i32(cu_video), max_n_text=max(Ls),
+                              max_n_keys=max(V + L for V, L in zip(Vs, Ls)), max_n_video=max(Vs),
+                              total_video=sum(Vs))
+        torch.cuda.synchronize()
+        for i in range(len(Vs)):
+            want = sum(per[l][i][0] for l in range(n_layers))
+            sl = slice(int(cu_video[i]), int(cu_video[i + 1]))
+            assert_scores_close(got[sl], want, f"request {i} mode{mode}")
+            assert_scores_close(got2[sl], want, f"request {i} mode{mode} row_lse")
+
+
+def test_score_layers_full_size_72b_all_80_layers(B):
+    """The benchmark's own launch: the 72B full-stack shape, all 80 verifier layers in one call.  Two layers
+    carry real queries in two kv-head groups each (the oracle sweeps those); every other (layer, group)
+    has zero queries, whose rows are uniform over the visible keys whatever the keys are: the closed form
+    1 / visible keys per column.  The keys of all 80 layers are random and distinct."""
+    w = synth.V72B_FULL
+    L, V, hq, hkv, d, n_layers = w.n_text, w.n_video, w.n_q_heads, w.n_kv_heads, w.head_dim, 80
+    group = hq // hkv
+    live = {3: (0, 5), 77: (2,)}
+    pos0 = V
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    kd = torch.randn((n_layers, V + L, hkv, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    qd = torch.zeros((n_layers, L, hq, d), dtype=torch.bfloat16, device="cuda")
+    want = np.zeros(V)
+    uniform = np.mean([1.0 / (pos0 + i + 1) for i in range(L)])      # text query i sees keys 0 .. pos0 + i
+    for layer, groups in live.items():
+        t = synth.make_layer(w, layer)
+        q, k = t["q_text"].copy(), t["k"][:V + L]
+        for g in range(hkv):
+            if g not in groups:
+                q[:, g * group:(g + 1) * group] = 0
+        qd[layer] = dev_bf16(q)
+        kd[layer] = dev_bf16(k)
+        for g in groups:
+            hs = slice(g * group, (g + 1) * group)
+            want += group * oracle.score(q[:, hs], k[:, g:g + 1], 0, V, pos0, w.softmax_scale, norm_mode=0)
+    n_live = sum(len(g) for g in live.values())
+    want = (want + (n_layers * hkv - n_live) * group * uniform) / hq
+    got = B.score_layers(qd, kd, 0, V, pos0, w.softmax_scale, norm_mode=0)
+    torch.cuda.synchronize()
+    # compared as the mean over the layers (Sec. 3.1's average), which has the magnitude the tolerances are written for
+    assert_scores_close(got / n_layers, want / n_layers, "72b-full, 80 layers in one call")
+
+
 def test_score_full_size_72b_layer_two_head_groups(B):
     """The 72B full-stack shape (256 text queries x 12 544 video keys, 64/8 heads, d 128) in the launch
     configuration the benchmark times.  The queries of all but two kv-head groups are zeroed: their rows
