@@ -407,10 +407,15 @@ def main():
         us_g = timed_replays(torch, graph_of(torch, lambda: B.gather_kv(k_all[:, :n_ctx], v_all[:, :n_ctx], 0, V, keep,
                                                                          k_dst=big_k, v_dst=big_v), args.eager), 10)
         big_bytes = 2 * 2 * L * n_pruned * hkv * d * 2
+        # beside it: the runtime's own contiguous device-to-device copy of as many bytes (K onto V), the yardstick
+        # for "a copy on this machine"
+        us_copy = timed_replays(torch, graph_of(torch, lambda: [big_v.copy_(big_k), big_v.copy_(big_k)], args.eager), 10)
         other[f"gather self-speculation shape ({L} layers x {n_pruned} kept rows x {hkv} kv heads d{d})"] = {
             "us": round(us_g, 1), "bytes_read_plus_written": big_bytes,
             "gbs": round(big_bytes / (us_g * 1e-6) / 1e9, 1),
-            "pct_of_hbm_peak": round(100.0 * big_bytes / (us_g * 1e-6) / 1e9 / HBM_PEAK_GBS, 1)}
+            "pct_of_hbm_peak": round(100.0 * big_bytes / (us_g * 1e-6) / 1e9 / HBM_PEAK_GBS, 1),
+            "plain_copy_of_as_many_bytes_us": round(us_copy, 1),
+            "plain_copy_gbs": round(big_bytes / (us_copy * 1e-6) / 1e9, 1)}
         del big_k, big_v
         # gather at the long-video configuration's sizes: 64 layers x 8 kv heads x d 128, 32 768 video + 256 text
         # tokens, keep 10 / 25 / 50 % (1.85 / 4.4 / 8.7 GB read + written); uninitialised buffers (a row copy does
