@@ -25,7 +25,8 @@ def test_abi_host_paths_under_asan_and_ubsan():
     env = dict(os.environ)
     env.update({
         "SPECVLM_LIB": lib,
-        "LD_PRELOAD": rt[0],                     # (replaces whatever was preloaded: the child makes no GPU call)
+        # the sanitizer runtime must come first in the list; whatever was preloaded stays behind it
+        "LD_PRELOAD": ":".join(x for x in (rt[0], os.environ.get("LD_PRELOAD", "")) if x),
         "ASAN_OPTIONS": "detect_leaks=0:abort_on_error=1:halt_on_error=1:protect_shadow_gap=0",
         "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1",
     })

@@ -27,7 +27,8 @@ def test_oracle_pins_under_asan_and_ubsan():
     env = dict(os.environ)
     env.update({
         "SPECVLM_ORACLE_SANITIZE": "1",
-        "LD_PRELOAD": asan,                      # (replaces whatever was preloaded: the child runs the CPU oracle only)
+        # the sanitizer runtime must come first in the list; whatever was preloaded stays behind it
+        "LD_PRELOAD": ":".join(x for x in (asan, os.environ.get("LD_PRELOAD", "")) if x),
         # the interpreter's own allocations are not the subject; any error in the oracle aborts the child
         "ASAN_OPTIONS": "detect_leaks=0:abort_on_error=1:halt_on_error=1",
         "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1",
