@@ -96,7 +96,7 @@ void select_kernel(const SelectParams p)
     int (*s_hist)[kSelCopies][kSelCopyWords] = reinterpret_cast<int (*)[kSelCopies][kSelCopyWords]>(s_hist_dyn);
     __shared__ int s_part[4][256];
     __shared__ int s_wave2[2][kSelWaves];
-    __shared__ int s_pick[2];
+    __shared__ int s_pick[3];
 
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -181,6 +181,7 @@ void select_kernel(const SelectParams p)
                         if (above < need && need <= above + c4[i]) {
                             s_pick[0] = 4 * lane + i;
                             s_pick[1] = need - above;
+                            s_pick[2] = (need - above == c4[i]);    // the whole bucket is taken: nothing left to rank
                         }
                         above += c4[i];
                     }
@@ -190,17 +191,22 @@ void select_kernel(const SelectParams p)
             prefix |= (uint32_t)s_pick[0] << shift;
             known |= 255u << shift;
             need = s_pick[1];
+            // When the keys that share the digits known so far are exactly as many as are still needed,
+            // all of them are taken and the lower digits decide nothing: the remaining passes are skipped
+            // (with distinct scores this is the usual case after three passes).
+            if (s_pick[2]) break;
         }
     }
-    // now: prefix = key of the k-th largest; take every key > prefix and the
-    // first `need` keys == prefix in index order.
+    // now: prefix = the known digits of the k-th largest key (all four, or fewer when a whole bucket
+    // is taken); take every key above it and the first `need` keys that share it, in index order.
     uint64_t gt = 0, eq = 0;
     if (k > 0) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             if (!((valid >> e) & 1)) continue;
-            if (key[e] > prefix) gt |= 1ull << e;
-            else if (key[e] == prefix) eq |= 1ull << e;
+            const uint32_t kk = key[e] & known;
+            if (kk > prefix) gt |= 1ull << e;
+            else if (kk == prefix) eq |= 1ull << e;
         }
     }
     // One block scan gives every thread the numbers of larger and of equal keys before its
