@@ -6,6 +6,7 @@
  * paper's tree decoding and ablations need:
  *
  *   specvlm_score        language-to-video attention scores   (Sec. 3.1, Eq. 4-5)
+ *   specvlm_score_layers the same, summed over all layers in one call
  *   specvlm_select       Stage I top-k + Stage II uniform stride (Sec. 3.2, Eq. 6-7)
  *   specvlm_top_p_count  Stage I's size by cumulative score mass (Sec. 3.2, Eq. 6)
  *   specvlm_gather_kv    the draft's pruned KV cache           (Sec. 3.2, last paragraph)
@@ -68,9 +69,9 @@ int specvlm_version(void);
  *
  * The guidance matrix G is the language-query x video-key block of the
  * verifier's attention matrix; a_j is column j of G averaged over the language
- * queries (Eq. 5) and over the q heads of this layer ("averaging across all
- * layers and heads": layers are accumulated by calling once per layer with
- * beta = 1).
+ * queries (Eq. 5) and over the q heads of this layer (Sec. 3.1 takes the mean
+ * over the layers as well: layers are accumulated by calling once per layer
+ * with beta = 1, or all at once by specvlm_score_layers).
  *
  *   q_text   bf16 [n_text, H_q, d]   language-prompt queries (RoPE already applied)
  *   k_cache  bf16 [n_keys, H_kv, d]  this layer's keys
