@@ -270,7 +270,9 @@ void select_kernel(const SelectParams p)
 // ---------------------------------------------------------------------------
 // Stage I's own size rule (Sec. 3.2, Eq. 6): the smallest c such that the c
 // largest scores reach lambda of the total score mass.  Same radix descent as
-// the selection, but the per-digit histograms carry SUMS as well as counts.
+// the selection, but the per-digit histograms carry the MASS of the keys, not
+// their number (the first pass's sums also give the total); the numbers of keys
+// above and at the threshold are counted once, at the end.
 // Sums are 64-bit fixed point (score * 2^40 / max score): integer adds commute,
 // so the result does not depend on the order in which lanes reach the atomics.
 // Scores are attention masses: a value that is not a finite positive number
@@ -284,18 +286,21 @@ struct TopPParams {
     int32_t* count;
 };
 
+constexpr size_t kTopPHistBytes = (size_t)kSelCopies * kSelCopyWords * sizeof(unsigned long long);   // one set
+
 template <int E>
 __global__ __launch_bounds__(kSelThreads)
 void top_p_kernel(const TopPParams p)
 {
-    __shared__ int s_cnt[kSelWaves][256];
-    __shared__ unsigned long long s_sum[kSelWaves][256];
-    __shared__ int s_tcnt[256];
-    __shared__ unsigned long long s_tsum[256];
+    // 64 copies of the 256 per-digit mass sums, one copy per lane of an instruction as in the selection
+    // (dynamic LDS); counts are not kept per digit: only the threshold key's are needed, at the end
+    extern __shared__ unsigned long long s_mass_dyn[];
+    unsigned long long (*s_mass)[kSelCopyWords] = reinterpret_cast<unsigned long long (*)[kSelCopyWords]>(s_mass_dyn);
+    __shared__ unsigned long long s_part[4][256];
     __shared__ float s_redf[kSelWaves];
-    __shared__ unsigned long long s_redu[kSelWaves];
-    __shared__ unsigned long long s_pick_sum;
-    __shared__ int s_pick[3];
+    __shared__ int s_redc[2][kSelWaves];
+    __shared__ unsigned long long s_pick_sum, s_goal;
+    __shared__ int s_pick;
 
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -310,6 +315,8 @@ void top_p_kernel(const TopPParams p)
     auto mass_of = [](float x) { return (x > 0.f && x < INFINITY) ? x : 0.f; };
     float val[E];
     load_run<E>(sc, first, per, n, val);
+    // the sums are cleared while the scores are on their way
+    for (int i = tid; i < kSelCopies * kSelCopyWords; i += kSelThreads) (&s_mass[0][0])[i] = 0ull;
     uint64_t valid = 0;
     float mx = 0.f;
 #pragma unroll
@@ -322,7 +329,7 @@ void top_p_kernel(const TopPParams p)
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if (lane == 0) s_redf[wave] = mx;
-    __syncthreads();
+    __syncthreads();                                    // (also: the cleared sums are visible)
     mx = 0.f;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) mx = fmaxf(mx, s_redf[w]);
@@ -333,89 +340,97 @@ void top_p_kernel(const TopPParams p)
     (void)frexpf(mx, &mx_exp);
     const int fix_shift = 40 - mx_exp;
     auto to_fix = [&](float x) { return (unsigned long long)ldexpf(mass_of(x), fix_shift); };
-    unsigned long long mine = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) mine += to_fix(val[e]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off);
-    if (lane == 0) s_redu[wave] = mine;
-    __syncthreads();
-    unsigned long long total = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) total += s_redu[w];
-    // goal = ceil(lambda * total); lambda is an fp32 in [0,1] and total < 2^56, so the double product
-    // is within a few units of 2^-40 of the largest score: far below the parity margin
-    const double goal_d = ceil((double)p.lambda * (double)total);
-    unsigned long long goal = goal_d <= 0.0 ? 0ull : (unsigned long long)goal_d;
-    if (goal > total) goal = total;
-    if (goal == 0) { if (tid == 0) p.count[b] = 0; return; }
 
     uint32_t prefix = 0, known = 0;
     unsigned long long above_sum = 0;          // mass of the keys known to rank above the threshold
-    int above_cnt = 0, eq_cnt = 0;
+    unsigned long long goal = 0;               // ceil(lambda * total), known once the first pass has the total
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        for (int i = tid; i < kSelWaves * 256; i += kSelThreads) {
-            (&s_cnt[0][0])[i] = 0;
-            (&s_sum[0][0])[i] = 0ull;
-        }
-        __syncthreads();
+        unsigned long long* const my_mass = &s_mass[(4 * wave + lane) & (kSelCopies - 1)][0];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             float x = val[e];
             __asm__ volatile("" : "+v"(x));          // recompute key and mass per pass: keeps them out of registers
             const uint32_t key = score_key(x);
             if (((valid >> e) & 1) && ((key & known) == prefix)) {
-                const int digit = (key >> shift) & 255;
-                atomicAdd(&s_cnt[wave][digit], 1);
-                atomicAdd(&s_sum[wave][digit], to_fix(x));
+                const unsigned long long m = to_fix(x);
+                if (m) atomicAdd(&my_mass[(key >> shift) & 255], m);
             }
         }
         __syncthreads();
-        if (tid < 256) {
-            int c = 0; unsigned long long sm = 0;
+        {
+            // thread (quarter, digit) sums a quarter of the digit's copies
+            const int digit = tid & 255, quarter = tid >> 8;
+            unsigned long long t = 0;
 #pragma unroll
-            for (int w = 0; w < kSelWaves; ++w) { c += s_cnt[w][tid]; sm += s_sum[w][tid]; }
-            s_tcnt[tid] = c; s_tsum[tid] = sm;
+            for (int w = 0; w < kSelCopies / 4; ++w) t += s_mass[quarter * (kSelCopies / 4) + w][digit];
+            s_part[quarter][digit] = t;
         }
         __syncthreads();
         if (wave == 0) {
             // lane l owns digits 4l..4l+3; inclusive suffix sums from the top digit down
-            int c4[4]; unsigned long long m4[4];
-            int cmine = 0; unsigned long long mmine = 0;
+            unsigned long long m4[4], mmine = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { c4[i] = s_tcnt[4 * lane + i]; m4[i] = s_tsum[4 * lane + i]; cmine += c4[i]; mmine += m4[i]; }
-            int cincl = cmine; unsigned long long mincl = mmine;
+            for (int i = 0; i < 4; ++i) {
+                m4[i] = s_part[0][4 * lane + i] + s_part[1][4 * lane + i] + s_part[2][4 * lane + i] + s_part[3][4 * lane + i];
+                mmine += m4[i];
+            }
+            unsigned long long mincl = mmine;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
-                const int yc = __shfl_down(cincl, off);
                 const unsigned long long ym = __shfl_down(mincl, off);
-                if (lane + off < 64) { cincl += yc; mincl += ym; }
+                if (lane + off < 64) mincl += ym;
+            }
+            if (pass == 0) {
+                // the first pass sees every key: lane 0's suffix sum is the total mass.
+                // goal = ceil(lambda * total); lambda is an fp32 in [0,1] and total < 2^56, so the double
+                // product is within a few units of 2^-40 of the largest score: far below the parity margin
+                const unsigned long long total = __shfl(mincl, 0);
+                const double goal_d = ceil((double)p.lambda * (double)total);
+                goal = goal_d <= 0.0 ? 0ull : (unsigned long long)goal_d;
+                if (goal > total) goal = total;
+                if (lane == 0) s_goal = goal;
             }
             // the threshold digit: first digit from the top where the running mass reaches the goal
             unsigned long long m_above = above_sum + (mincl - mmine);
-            int c_above = above_cnt + (cincl - cmine);
-            if (m_above < goal && goal <= above_sum + mincl) {
+            if (goal > 0 && m_above < goal && goal <= above_sum + mincl) {
 #pragma unroll
                 for (int i = 3; i >= 0; --i) {
-                    if (m_above < goal && goal <= m_above + m4[i]) {
-                        s_pick[0] = 4 * lane + i; s_pick[1] = c_above; s_pick[2] = c4[i];
-                        s_pick_sum = m_above;
-                    }
-                    m_above += m4[i]; c_above += c4[i];
+                    if (m_above < goal && goal <= m_above + m4[i]) { s_pick = 4 * lane + i; s_pick_sum = m_above; }
+                    m_above += m4[i];
                 }
             }
+        } else if (pass < 3) {
+            // (the sums were read for the last time before the barrier above: cleared for the next pass)
+            for (int i = tid - kWave; i < kSelCopies * kSelCopyWords; i += kSelThreads - kWave) (&s_mass[0][0])[i] = 0ull;
         }
         __syncthreads();
-        prefix |= (uint32_t)s_pick[0] << shift;
+        if (pass == 0) {
+            goal = s_goal;
+            if (goal == 0) { if (tid == 0) p.count[b] = 0; return; }
+        }
+        prefix |= (uint32_t)s_pick << shift;
         known |= 255u << shift;
-        above_cnt = s_pick[1]; eq_cnt = s_pick[2]; above_sum = s_pick_sum;
+        above_sum = s_pick_sum;
     }
+    // prefix is now the threshold key: count the keys above it and those equal to it
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const uint32_t key = score_key(val[e]);
+        if ((valid >> e) & 1) { gt += key > prefix; eq += key == prefix; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { gt += __shfl_xor(gt, off); eq += __shfl_xor(eq, off); }
+    if (lane == 0) { s_redc[0][wave] = gt; s_redc[1][wave] = eq; }
+    __syncthreads();
     if (tid == 0) {
+        int above_cnt = 0, eq_cnt = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) { above_cnt += s_redc[0][w]; eq_cnt += s_redc[1][w]; }
         // every key equal to the threshold carries the same mass: take as many as the goal needs
-        float tval = 0.f;
         const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
-        tval = __uint_as_float(u);
+        const float tval = __uint_as_float(u);
         const unsigned long long each = to_fix(tval);
         const unsigned long long need = goal - above_sum;
         long long take = each > 0 ? (long long)((need + each - 1) / each) : eq_cnt;
@@ -443,6 +458,23 @@ static int launch_select(int batch, const SelectParams& p, hipStream_t stream)
         raised[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(select_kernel<E>, dim3(batch), dim3(kSelThreads), kSelHistBytes, stream, p);
+    return SPECVLM_OK;
+}
+
+template <int E>
+static int launch_top_p(int batch, const TopPParams& p, hipStream_t stream)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> raised[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECVLM_ELAUNCH;
+    if (!raised[dev].load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&top_p_kernel<E>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTopPHistBytes) != hipSuccess)
+            return SPECVLM_ELAUNCH;
+        raised[dev].store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(top_p_kernel<E>, dim3(batch), dim3(kSelThreads), kTopPHistBytes, stream, p);
     return SPECVLM_OK;
 }
 
@@ -514,9 +546,11 @@ extern "C" int specvlm_top_p_count(
     p.lambda = lambda; p.max_count = max_count; p.count = count;
     hipStream_t s = (hipStream_t)stream;
     const int per = (max_n_video + kSelThreads - 1) / kSelThreads;
-    if (per <= 4)       hipLaunchKernelGGL(top_p_kernel<4>,  dim3(batch), dim3(kSelThreads), 0, s, p);
-    else if (per <= 16) hipLaunchKernelGGL(top_p_kernel<16>, dim3(batch), dim3(kSelThreads), 0, s, p);
-    else if (per <= 32) hipLaunchKernelGGL(top_p_kernel<32>, dim3(batch), dim3(kSelThreads), 0, s, p);
-    else                hipLaunchKernelGGL(top_p_kernel<64>, dim3(batch), dim3(kSelThreads), 0, s, p);
+    int rc;
+    if (per <= 4)       rc = launch_top_p<4>(batch, p, s);
+    else if (per <= 16) rc = launch_top_p<16>(batch, p, s);
+    else if (per <= 32) rc = launch_top_p<32>(batch, p, s);
+    else                rc = launch_top_p<64>(batch, p, s);
+    if (rc != SPECVLM_OK) return rc;
     return launch_status();
 }

@@ -182,6 +182,27 @@ def test_select_ragged_batches(B):
             o += buds[i]
 
 
+def test_top_p_counts(B):
+    """Eq. 6's count on random sizes, score shapes (long-tailed, tied, a narrow band, signs / NaN / -0) and
+    mass fractions; equality with the oracle wherever lambda * total is further than 1e-6 * total from a
+    deciding prefix sum, at most one apart inside that margin."""
+    rng = np.random.default_rng(1109)
+    checked = 0
+    for it in range(24):
+        n = int(rng.integers(1, 65537)) if rng.integers(3) else int(rng.integers(1, 3000))
+        s = random_scores(rng, n)
+        lam = float(np.float32(rng.choice([0.02, 0.1, 0.3, 0.5, 0.8, 0.97])))
+        want, margin = oracle.top_p_count(s, lam, want_margin=True)
+        got = B.top_p_count(torch.from_numpy(s).cuda(), lam).item()
+        torch.cuda.synchronize()
+        if margin > 1e-6:
+            assert got == want, (it, n, lam, got, want, margin)
+            checked += 1
+        else:
+            assert abs(got - want) <= 1, (it, n, lam, got, want, margin)
+    assert checked >= 12
+
+
 def test_gather_rows(B):
     rng = np.random.default_rng(1107)
     for it in range(10):
