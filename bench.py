@@ -398,6 +398,10 @@ def main():
         acc_bytes = (2 * w3.gamma + 1) * w3.vocab * 4
         other["accept sampling gamma 7 vocab 152064"] = {"us": round(us3, 2), "bytes": acc_bytes,
                                                          "gbs": round(acc_bytes / (us3 * 1e-6) / 1e9, 1)}
+        # Stage I sized by cumulative score mass (Eq. 6) on the step's own scores
+        cnt = torch.empty(1, dtype=torch.int32, device=dev)
+        us_tp = repeated_us(lambda: B.top_p_count(scores, 0.3, count=cnt))
+        other[f"top_p_count lambda 0.3 over {V} video tokens"] = {"us": round(us_tp, 2), "count": int(cnt.item())}
         # gather at the self-speculation shape: the verifier's own cache (all layers, 8 kv heads, d 128), keep 10 %
         if args.layout == "head-major":
             big_k = torch.empty((L, hkv, n_pruned, d), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
