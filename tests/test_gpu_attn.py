@@ -55,8 +55,8 @@ def run_case(B, q_len, kv_len, hq, hkv, d, seed, num_splits=0, scale=None, head_
     (4, 515, 40, 8, 128, 0),
     (6, 6, 8, 1, 128, 0),          # cache holds only the block itself
     (3, 130, 2, 2, 64, 0),         # group 1
-    (6, 9000, 8, 1, 128, 70),      # more splits than the merge kernel prefetches per thread group (d 128: 48)
-    (2, 9000, 4, 1, 64, 70),       # the same for d 64 (prefetch covers 64)
+    (6, 9000, 8, 1, 128, 70),      # more splits than the merge kernel prefetches (12 groups x 3 = 36)
+    (2, 9000, 4, 1, 64, 70),       # the same for d 64
     (6, 200, 8, 1, 128, 1),        # one split of three tiles and a bit: the ring wraps once
     (6, 70, 16, 2, 128, 0),        # a split shorter than the ring: its last tile is loaded twice
     (9, 900, 8, 1, 64, 0),         # 72 rows per kv head: two groups of three row blocks
